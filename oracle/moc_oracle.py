@@ -1,0 +1,231 @@
+"""CPU oracle for the Mixture-of-Channels (MoC) feed-forward layer.  TEST INFRASTRUCTURE ONLY.
+
+Plain numpy, float64, written from the paper's equations in the paper's notation:
+X is [s, d], W_gate and W_up are [d, d_ffn], W_down is [d_ffn, d].  Nothing here is
+blocked, fused or reordered, and nothing is shared with the HIP kernels.  Only tests,
+the smoke check and the benchmark's cpu_baseline leg may import this module; the
+product never does.
+
+What each function follows:
+  silu, silu_grad          Section "SiLU activation pattern", Eq. (3); the derivative is the
+                           textbook one of that formula (the paper names the operator only).
+  swiglu_forward/backward  Section "Activation memory profiling", Eqs. (FFN-1), (FFN-2).
+  topk_mask                Section "Mixture-of-Channels architecture": M = TopK(G), row-wise,
+                           largest signed values, exactly K ones per row.
+  moc_forward*             Eqs. (MoC-1), (MoC-2).
+  moc_backward             Section "Activation-efficient pre-training", Eqs. (bp-1)...(bp-5),
+                           with S' and Z' recomputed from the stored G.M and U.M (MoC + GCP).
+  moc_decode               Section "Accelerated inference", the four-step per-token recipe.
+  rmsnorm, residual_add    Section "Activation memory profiling", RMSNorm and residual items.
+
+Readings where the paper is silent (also listed in the design notes):
+  * ties at the K-th value: the lower channel index wins; -0.0 and +0.0 are equal;
+  * the selection is decided on the gate rounded to float32 (the precision the HIP path
+    selects in), everything else stays float64;
+  * compact form of the stored set: idx ascending by channel, gvals = G at idx, uvals = U at idx.
+
+Pins (tests/test_oracle_*.py): a hand-worked example from Eq. (3) and (MoC-2), brute-force
+full-sort selection, numpy/torch library selection routines, dense SwiGLU through torch's own
+silu at K = d_ffn, torch.autograd and central finite differences for the backward, torch's
+rms_norm, and the invariants (unselected channels contribute nothing, token independence,
+channel-permutation equivariance, decode == training forward).  No function here is unpinned.
+"""
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a):
+    return np.asarray(a, dtype=F64)
+
+
+# --------------------------------------------------------------------------- Eq. (3)
+def silu(x):
+    x = _f64(x)
+    with np.errstate(over="ignore"):
+        return x / (1.0 + np.exp(-x))
+
+
+def sigmoid(x):
+    x = _f64(x)
+    with np.errstate(over="ignore"):
+        return 1.0 / (1.0 + np.exp(-x))
+
+
+def silu_grad(x):
+    """d/dx [x * sigmoid(x)] = sigmoid(x) * (1 + x * (1 - sigmoid(x)))."""
+    x = _f64(x)
+    sg = sigmoid(x)
+    return sg * (1.0 + x * (1.0 - sg))
+
+
+# ------------------------------------------------------------------ Eqs. (FFN-1), (FFN-2)
+def swiglu_forward(X, W_gate, W_up, W_down):
+    X, W_gate, W_up, W_down = map(_f64, (X, W_gate, W_up, W_down))
+    G = X @ W_gate
+    U = X @ W_up
+    S = silu(G)
+    Z = S * U
+    D = Z @ W_down
+    return D, G, U
+
+
+def swiglu_backward(X, W_gate, W_up, W_down, G, U, dD):
+    """Gradients of the dense FFN given its stored G and U (Eqs. (bp-1)...(bp-5) with M = 1)."""
+    ones = np.ones(np.shape(G), dtype=bool)
+    return moc_backward(X, W_gate, W_up, W_down, ones, G, U, dD)
+
+
+# ------------------------------------------------------------------------ M = TopK(G)
+def topk_mask(G, K, select_dtype=np.float32):
+    """Boolean mask with exactly K ones per row marking the K largest signed entries.
+
+    The decision is taken on G cast to `select_dtype`.  Equal values are ordered by
+    channel index, lower first (stable sort on the negated row).
+    """
+    G = np.asarray(G)
+    s, F = G.shape
+    if not (1 <= K <= F):
+        raise ValueError("K must satisfy 1 <= K <= d_ffn")
+    if not np.all(np.isfinite(G)):
+        raise ValueError("non-finite gate values")
+    key = G.astype(select_dtype)
+    M = np.zeros((s, F), dtype=bool)
+    for i in range(s):
+        order = np.argsort(-key[i], kind="stable")
+        M[i, order[:K]] = True
+    return M
+
+
+# ------------------------------------------------------------- Eqs. (MoC-1), (MoC-2)
+def moc_forward_given_mask(X, W_gate, W_up, W_down, M):
+    X, W_gate, W_up, W_down = map(_f64, (X, W_gate, W_up, W_down))
+    G = X @ W_gate
+    U = X @ W_up
+    S = silu(G)
+    S_prime = S * M
+    Z_prime = S_prime * U
+    D = Z_prime @ W_down
+    return D, G, U
+
+
+def moc_forward(X, W_gate, W_up, W_down, K):
+    G = _f64(X) @ _f64(W_gate)
+    M = topk_mask(G, K)
+    D, G, U = moc_forward_given_mask(X, W_gate, W_up, W_down, M)
+    return D, M, G, U
+
+
+# ------------------------------------------------ compact stored set (Table 1, MoC+GCP)
+def compact_saved(M, G, U):
+    """(idx, gvals, uvals), each [s, K]: the ones of M in ascending channel order, G and U there."""
+    s, F = M.shape
+    K = int(M[0].sum())
+    idx = np.empty((s, K), dtype=np.int32)
+    for i in range(s):
+        cols = np.flatnonzero(M[i])
+        if cols.size != K:
+            raise ValueError("mask rows must all hold K ones")
+        idx[i] = cols
+    rows = np.arange(s)[:, None]
+    return idx, _f64(G)[rows, idx], _f64(U)[rows, idx]
+
+
+def expand_saved(idx, gvals, uvals, F):
+    """Inverse of compact_saved: M, G.M and U.M as dense [s, d_ffn] arrays."""
+    idx = np.asarray(idx)
+    s, K = idx.shape
+    rows = np.arange(s)[:, None]
+    M = np.zeros((s, F), dtype=bool)
+    M[rows, idx] = True
+    GM = np.zeros((s, F), dtype=F64)
+    UM = np.zeros((s, F), dtype=F64)
+    GM[rows, idx] = _f64(gvals)
+    UM[rows, idx] = _f64(uvals)
+    return M, GM, UM
+
+
+def mask_from_idx(idx, F):
+    idx = np.asarray(idx)
+    M = np.zeros((idx.shape[0], F), dtype=bool)
+    M[np.arange(idx.shape[0])[:, None], idx] = True
+    return M
+
+
+# ------------------------------------------------------------ Eqs. (bp-1) ... (bp-5)
+def moc_backward(X, W_gate, W_up, W_down, M, GM, UM, dD):
+    """Backward of the MoC layer from the stored set {M, G.M, U.M} and the upstream gradient.
+
+    S' and Z' are recomputed from G.M (gradient checkpointing of the two element-wise steps).
+    Returns (dX, dW_gate, dW_up, dW_down) in the paper's shapes.
+    """
+    X, W_gate, W_up, W_down, GM, UM, dD = map(_f64, (X, W_gate, W_up, W_down, GM, UM, dD))
+    M = np.asarray(M, dtype=bool)
+    S_prime = silu(GM) * M                      # S' = SiLU(G) . M
+    Z_prime = S_prime * UM                      # Z' = S' . U
+    dW_down = Z_prime.T @ dD                    # (bp-1)
+    dZ_prime = dD @ W_down.T                    # (bp-1)
+    dS_prime = (UM * M) * dZ_prime              # (bp-2)
+    dU = S_prime * dZ_prime                     # (bp-2)
+    dS = dS_prime                               # (bp-3)
+    dG = dS * silu_grad(GM)                     # (bp-3)
+    dW_gate = X.T @ dG                          # (bp-4)
+    dW_up = X.T @ dU                            # (bp-4)
+    dX = dG @ W_gate.T + dU @ W_up.T            # (bp-5)
+    return dX, dW_gate, dW_up, dW_down
+
+
+# -------------------------------------------------- inference recipe, one token at a time
+def moc_decode(x, W_gate, W_up, W_down, K):
+    """Per-token recipe: g = x W_gate, Top-K set C, z'_j = SiLU(g_j) (x . W_up[:, j]) for j in C,
+    d = sum_{j in C} z'_j w_j with w_j the j-th row of W_down.  Only the K selected columns of
+    W_up and rows of W_down are touched.  x may be [d] or [B, d]; tokens are independent."""
+    x = _f64(x)
+    single = x.ndim == 1
+    xs = x[None, :] if single else x
+    W_gate, W_up, W_down = map(_f64, (W_gate, W_up, W_down))
+    B, d = xs.shape
+    out = np.zeros((B, d), dtype=F64)
+    sets = np.empty((B, K), dtype=np.int32)
+    for b in range(B):
+        g = xs[b] @ W_gate
+        C = np.flatnonzero(topk_mask(g[None, :], K)[0])
+        u_C = xs[b] @ W_up[:, C]
+        z_C = silu(g[C]) * u_C
+        acc = np.zeros(d, dtype=F64)
+        for zj, j in zip(z_C, C):
+            acc += zj * W_down[j]
+        out[b] = acc
+        sets[b] = C
+    return (out[0], sets[0]) if single else (out, sets)
+
+
+def decode_macs(d, d_ffn, K):
+    """Multiply-accumulates per token: dense FFN and MoC (section "Accelerated inference")."""
+    return 3 * d * d_ffn, d * d_ffn + 2 * K * d
+
+
+def stored_activation_elements(s, d_ffn, K):
+    """Elements of the MoC+GCP stored set besides D: M, G.M and U.M kept compactly (Table 1)."""
+    return 3 * s * K
+
+
+# ----------------------------------------------------------- RMSNorm, residual, the stack
+def rmsnorm(x, gain, eps):
+    x = _f64(x)
+    rms = np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    return x / rms * _f64(gain)
+
+
+def residual_add(x, y):
+    return _f64(x) + _f64(y)
+
+
+def prefill_stack(h, layers, K, eps):
+    """h <- h + MoC_l(RMSNorm(h)) for every layer; layers = [(gain, W_gate, W_up, W_down), ...]."""
+    h = _f64(h)
+    for gain, W_gate, W_up, W_down in layers:
+        xn = rmsnorm(h, gain, eps)
+        D, _, _, _ = moc_forward(xn, W_gate, W_up, W_down, K)
+        h = residual_add(h, D)
+    return h
