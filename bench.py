@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoC FFN hot path on one MI355X.
+
+A step is one training forward + backward of one MoC FFN layer (all kernels of moc_ffn_fwd and
+moc_ffn_bwd) over one batch of seeded synthetic tokens at the "1B shape" (T 8192, d 2048,
+d_ff 5461, K 683, bf16 with fp32 accumulation), inputs resident in HBM.  The JSON line also
+carries the decode leg at the "7B shape" (effective HBM GB/s, cold weights), a per-kernel
+breakdown, the roofline entry of the gate GEMM and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    return ap.parse_args()
+
+
+def gemm_flops(T, d, F, K):
+    """Executed and algorithmic FLOPs per launch of every GEMM-shaped kernel of one step."""
+    ex = 2.0 * T * d * F
+    al = 2.0 * T * d * K
+    return {
+        "gemm_gate": (ex, ex),                       # truly dense: algorithmic == executed
+        "gemm_up": (ex, al),
+        "gemm_down": (ex, al),
+        "gemm_dz_pointwise": (ex, al),
+        "gemm_dwd": (ex, al),
+        "gemm_dwg": (ex, al),
+        "gemm_dwu": (ex, al),
+        "gemm_dx": (2 * ex, 2 * al),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards over tokens; see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2511_09323_amd as moc
+    from paper_2511_09323_amd import inputs
+    from paper_2511_09323_amd.configs import CONFIGS, DECODE_BATCHES
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    moc.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = CONFIGS[args.workload]
+    cfg_index = int(args.workload[-1])
+    T, d, F, K = cfg.T, cfg.d, cfg.F, cfg.K
+    bf = torch.bfloat16
+
+    def dev_bf16(a):
+        return torch.from_numpy(a).to(dev).to(bf).contiguous()
+
+    L = inputs.make_layer(cfg_index, T, d, F, "bf16", with_dy=True)
+    G = {k: dev_bf16(v) for k, v in L.items()}
+    ws_f = torch.empty(moc.workspace_bytes(T, d, F, K, bf, 0), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(moc.workspace_bytes(T, d, F, K, bf, 1), dtype=torch.uint8, device=dev)
+    out_f = (torch.empty((T, d), dtype=bf, device=dev), torch.empty((T, K), dtype=torch.int32, device=dev),
+             torch.empty((T, K), dtype=bf, device=dev), torch.empty((T, K), dtype=bf, device=dev))
+    out_b = (torch.empty((T, d), dtype=bf, device=dev), torch.empty((F, d), dtype=bf, device=dev),
+             torch.empty((F, d), dtype=bf, device=dev), torch.empty((F, d), dtype=bf, device=dev))
+
+    def step():
+        y, idx, gv, uv = moc.moc_ffn_fwd(G["x"], G["wg"], G["wu"], G["wd"], K, ws=ws_f, out=out_f)
+        moc.moc_ffn_bwd(G["x"], G["wg"], G["wu"], G["wd"], idx, gv, uv, G["dy"], ws=ws_b, out=out_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = T / (ms_per_step * 1e-3)
+
+    # per-kernel durations: the same steps again with HIP events around every launch, recorded
+    # by the library on the stream the kernels run on
+    moc.timing_reset()
+    moc.timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    timing = moc.timing_read()
+    moc.timing_enable(False)
+    moc.timing_reset()
+    flops = gemm_flops(T, d, F, K)
+    kernels = []
+    for name, (ms, n) in sorted(timing.items(), key=lambda kv: -kv[1][0]):
+        avg_ms = ms / max(n, 1)
+        row = {"kernel": name, "avg_ms": round(avg_ms, 5), "launches": n}
+        if name in flops:
+            ex, al = flops[name]
+            row["executed_tflops"] = round(ex / (avg_ms * 1e-3) / 1e12, 2)
+            row["algorithmic_tflops"] = round(al / (avg_ms * 1e-3) / 1e12, 2)
+            row["frac_executed"] = round(row["executed_tflops"] / PEAK_BF16_TFLOPS, 4)
+        kernels.append(row)
+    gate = next((r for r in kernels if r["kernel"] == "gemm_gate"), None)
+    roofline = None
+    if gate:
+        roofline = {"kernel": "gemm_gate", "bound": "mfma", "achieved": gate["executed_tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(gate["executed_tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "avg_ms": gate["avg_ms"]}
+    gemm_ms = sum(r["avg_ms"] for r in kernels if r["kernel"] in flops)
+    gemm_ex = sum(flops[r["kernel"]][0] for r in kernels if r["kernel"] in flops)
+    gemm_al = sum(flops[r["kernel"]][1] for r in kernels if r["kernel"] in flops)
+    all_gemms = {"sum_avg_ms": round(gemm_ms, 4),
+                 "executed_tflops": round(gemm_ex / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms else None,
+                 "algorithmic_tflops": round(gemm_al / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms else None}
+
+    # dense SwiGLU through the same library, for the paper's dense-vs-MoC comparison
+    dense = None
+    if not args.no_dense:
+        ws_df = torch.empty(moc.workspace_bytes(T, d, F, F, bf, 3), dtype=torch.uint8, device=dev)
+        ws_db = torch.empty(moc.workspace_bytes(T, d, F, F, bf, 4), dtype=torch.uint8, device=dev)
+        out_df = (out_f[0], torch.empty((T, F), dtype=bf, device=dev), torch.empty((T, F), dtype=bf, device=dev))
+
+        def dense_step():
+            y, gs, us = moc.moc_swiglu_fwd(G["x"], G["wg"], G["wu"], G["wd"], ws=ws_df, out=out_df)
+            moc.moc_swiglu_bwd(G["x"], G["wg"], G["wu"], G["wd"], gs, us, G["dy"], ws=ws_db, out=out_b)
+
+        for _ in range(max(2, args.warmup // 2)):
+            dense_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_dense = max(3, args.steps // 2)
+        for _ in range(n_dense):
+            dense_step()
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t0) * 1e3 / n_dense
+        dense = {"ms_per_step": round(dense_ms, 4), "tokens_per_s": round(T / (dense_ms * 1e-3), 1),
+                 "saved_activation_bytes": 2 * T * F * 2, "moc_saved_activation_bytes": T * K * (4 + 2 * 2)}
+        del ws_df, ws_db, out_df
+
+    # decode leg: 7B shape, cold weights (rotating through independent weight sets)
+    decode = None
+    if not args.no_decode:
+        decode = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
+
+    line = {
+        "metric": "MoC FFN fwd+bwd tokens/s (1B shape) + decode effective HBM GB/s vs peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
+                   "T": T, "d_model": d, "d_ff": F, "K": K},
+        "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
+        "decode": decode,
+    }
+    print(json.dumps(line))
+
+
+def decode_leg(torch, moc, inputs, cfg, batches, dev):
+    d, F, K = cfg.d, cfg.F, cfg.K
+    bf = torch.bfloat16
+    R = 8        # independent weight sets: 8 x 270 MB >> the 256 MB last-level cache, so every call is cold
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(30_000)
+    sets = []
+    for r in range(R):
+        sets.append(tuple((torch.randn((F, d), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(bf)
+                          for _ in range(3)))
+    out = []
+    for B in batches:
+        xs = [torch.randn((B, d), generator=gen, device=dev, dtype=torch.float32).to(bf) for _ in range(R)]
+        ws = torch.empty(moc.workspace_bytes(B, d, F, K, bf, 2), dtype=torch.uint8, device=dev)
+        y = torch.empty((B, d), dtype=bf, device=dev)
+        idx = torch.empty((B, K), dtype=torch.int32, device=dev)
+        unions = []
+        for r in range(R):
+            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+            torch.cuda.synchronize()
+            unions.append(int(torch.unique(idx).numel()))
+        union = float(np.mean(unions))
+        algo_bytes = d * F * 2 + 2 * union * d * 2 + 2 * B * d * 2
+        iters = 5 * R
+        start = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+        stop = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+        for i in range(iters):
+            r = i % R
+            start[i].record()
+            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+            stop[i].record()
+        torch.cuda.synchronize()
+        us = sorted(s.elapsed_time(e) * 1e3 for s, e in zip(start, stop))
+        med = us[len(us) // 2]
+        # warm: the same weight set every call (cache-resident, reported separately)
+        for _ in range(3):
+            moc.moc_ffn_decode(xs[0], *sets[0], K, ws=ws, out=(y, idx))
+        torch.cuda.synchronize()
+        s0, e0 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for _ in range(20):
+            moc.moc_ffn_decode(xs[0], *sets[0], K, ws=ws, out=(y, idx))
+        e0.record()
+        torch.cuda.synchronize()
+        warm_us = s0.elapsed_time(e0) * 1e3 / 20
+        gbs = algo_bytes / (med * 1e-6) / 1e9
+        out.append({"B": B, "cold_us_median": round(med, 2), "cold_us_min": round(us[0], 2), "warm_us": round(warm_us, 2),
+                    "union_channels": round(union, 1), "algorithmic_MB": round(algo_bytes / 1e6, 2),
+                    "effective_GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
+    return {"workload": "cfg3: d_model=%d d_ff=%d K=%d bf16, cold weights (8 rotating sets)" % (d, F, K), "batches": out}
+
+
+def cpu_baseline(L, K, sample_tokens):
+    """The CPU oracle as it stands (numpy float64), timed on the first `sample_tokens` tokens of the
+    same workload: forward (own selection) + backward, full-size weights."""
+    from oracle import moc_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n = min(sample_tokens, L["x"].shape[0])
+    X = L["x"][:n].astype(np.float64)
+    dY = L["dy"][:n].astype(np.float64)
+    Wg, Wu, Wd = L["wg"].astype(np.float64).T, L["wu"].astype(np.float64).T, L["wd"].astype(np.float64)
+    t0 = time.perf_counter()
+    D, M, Gm, U = O.moc_forward(X, Wg, Wu, Wd, K)
+    O.moc_backward(X, Wg, Wu, Wd, M, Gm * M, U * M, dY)
+    dt = time.perf_counter() - t0
+    return {"value": round(n / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d tokens of the same layer, forward + backward, numpy float64, %.1f s" % (n, dt)}
+
+
+if __name__ == "__main__":
+    main()

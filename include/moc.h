@@ -1,0 +1,136 @@
+/*
+ * moc.h -- C ABI of the Mixture-of-Channels (MoC) feed-forward layer for AMD MI355X (gfx950).
+ *
+ * The layer (paper section "Mixture-of-Channels architecture", Eqs. (MoC-1), (MoC-2)):
+ *     G = X W_gate,  U = X W_up,  M = TopK(G) row-wise on the signed, pre-SiLU gate,
+ *     S' = SiLU(G) . M,  Z' = S' . U,  D = Z' W_down.
+ * Backward: section "Activation-efficient pre-training", Eqs. (bp-1)...(bp-5), with the
+ * MoC+GCP stored set of Table 1 (G.M, U.M and M; S' and Z' are recomputed).
+ * Decode: section "Accelerated inference", the per-token recipe that touches only K columns of
+ * W_up and K rows of W_down.
+ *
+ * Conventions shared by every entry point
+ *  - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned, valid on the
+ *    device that is current when the call is made.  The shape struct is HOST memory.
+ *  - Layouts (row-major, tight): x, y, dy, dx are [T, d].  The three weights and their gradients
+ *    are channel-major [F, d]: row j of wg / wu is column j of the paper's W_gate / W_up, row j of
+ *    wd is row j of W_down.  idx, gvals, uvals are [T, K]; within a row idx ascends by channel and
+ *    gvals / uvals hold G and U at those channels (the paper's G.M, U.M and M in compact form).
+ *  - dtype is the element type of x, the weights, y, the saved values and all gradients
+ *    (MOC_F32 or MOC_BF16).  All accumulation is fp32.  The Top-K decision is taken on the fp32
+ *    gate accumulator before any rounding; equal values are ordered by channel, lower first,
+ *    and -0.0 equals +0.0.  Non-finite inputs are not detected.
+ *  - The library allocates no device memory and keeps no state between calls; scratch lives in
+ *    the caller's workspace `ws` of at least moc_workspace_bytes(shape, op) bytes (256-byte
+ *    aligned).  Two calls that overlap in time must not share a workspace.
+ *  - Calls validate their arguments on the host, enqueue kernels on `hip_stream` (a hipStream_t,
+ *    NULL = the default stream) and return without synchronising; outputs are valid in stream
+ *    order.  Gradients are overwritten, not accumulated.
+ *  - Errors: a negative moc_status is returned and moc_last_error() describes it (thread-local
+ *    text).  Argument errors are found before anything is launched and leave outputs untouched.
+ *  - Limits: 1 <= K <= F <= 32768, T >= 1 (T <= 16 for decode), d >= 1; MOC_BF16 needs d % 8 == 0.
+ */
+#ifndef MOC_H
+#define MOC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOC_OK = 0,
+    MOC_ERR_BAD_ARG = -1,      /* null / misaligned pointer, K or shape out of range, unknown dtype */
+    MOC_ERR_WORKSPACE = -2,    /* ws_bytes smaller than moc_workspace_bytes() */
+    MOC_ERR_UNSUPPORTED = -3,  /* valid request this build cannot run (e.g. F too large for LDS) */
+    MOC_ERR_HIP = -4           /* a HIP runtime call failed; text holds hipGetErrorString */
+} moc_status;
+
+typedef enum { MOC_F32 = 0, MOC_BF16 = 1 } moc_dtype;
+
+typedef enum {
+    MOC_OP_FWD = 0,
+    MOC_OP_BWD = 1,
+    MOC_OP_DECODE = 2,
+    MOC_OP_SWIGLU_FWD = 3,
+    MOC_OP_SWIGLU_BWD = 4
+} moc_op;
+
+/* T tokens (batch for decode), d = d_model, F = d_ffn, K selected channels per token. */
+typedef struct {
+    int32_t T, d, F, K;
+    int32_t dtype; /* moc_dtype */
+} moc_shape;
+
+/* Bytes of workspace `op` needs for `shape`; 0 if the shape is invalid. */
+size_t moc_workspace_bytes(const moc_shape* shape, int op);
+
+/* Training forward, Eqs. (MoC-1), (MoC-2).  Writes y[T,d] and the stored set idx[T,K] (int32),
+ * gvals[T,K], uvals[T,K] (dtype).  Steps: gate projection (fp32), row Top-K, up projection,
+ * SiLU(g).u on the selected channels, down projection. */
+moc_status moc_ffn_fwd(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                       const void* wd, void* y, int32_t* idx, void* gvals, void* uvals,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Training backward, Eqs. (bp-1)...(bp-5), from the stored set and dy[T,d].  Writes dx[T,d] and
+ * dwg, dwu, dwd [F,d].  idx rows must ascend strictly and lie in [0, F). */
+moc_status moc_ffn_bwd(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                       const void* wd, const int32_t* idx, const void* gvals, const void* uvals,
+                       const void* dy, void* dx, void* dwg, void* dwu, void* dwd,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Decode, section "Accelerated inference": shape->T is the batch B (1..16).  Reads all of wg and
+ * only the rows of wu and wd that some token selected.  Writes y[B,d]; if idx_or_null is not
+ * NULL also the selected channels idx[B,K] (ascending). */
+moc_status moc_ffn_decode(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                          const void* wd, void* y, int32_t* idx_or_null,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Dense SwiGLU FFN, Eqs. (FFN-1), (FFN-2): the K = F reference.  shape->K is ignored.
+ * g_save, u_save are [T,F] in dtype (the dense stored set G and U). */
+moc_status moc_swiglu_fwd(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                          const void* wd, void* y, void* g_save, void* u_save,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_swiglu_bwd(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                          const void* wd, const void* g_save, const void* u_save, const void* dy,
+                          void* dx, void* dwg, void* dwu, void* dwd,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Row-wise Top-K alone (the mask definition of section "Mixture-of-Channels architecture"):
+ * g[T, ldg] fp32 (ldg >= F elements) -> idx[T,K] ascending by channel and gsel[T,K] fp32, the gate
+ * values there.  Needs no workspace. */
+moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_t ldg,
+                         int32_t* idx, float* gsel, void* hip_stream);
+
+/* RMSNorm of each row, y = x / sqrt(mean(x^2) + eps) . gain (section "Activation memory
+ * profiling", RMSNorm item); h, out are [T,d] in dtype, gain is [d] in dtype. */
+moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain,
+                       float eps, void* out, void* hip_stream);
+
+/* Residual connection h <- h + y on [T,d] (same section, residual item). */
+moc_status moc_residual_add(int32_t T, int32_t d, int32_t dtype, void* h_inout, const void* y,
+                            void* hip_stream);
+
+/* Per-kernel timing for benchmarks.  moc_timing_enable(1) makes every later call bracket each
+ * kernel launch with HIP events on the call's stream; moc_timing_collect synchronises those
+ * events, adds their durations to the per-kernel totals and returns the number of distinct
+ * kernel names seen so far.  moc_timing_get copies entry i (name up to name_cap-1 chars, total
+ * milliseconds, launch count).  moc_timing_enable(0) stops recording; moc_timing_reset clears
+ * the totals.  HOST pointers.  Not thread-safe. */
+void moc_timing_enable(int on);
+int32_t moc_timing_collect(void);
+moc_status moc_timing_get(int32_t i, char* name, int32_t name_cap, double* total_ms, int64_t* launches);
+void moc_timing_reset(void);
+
+const char* moc_status_string(int status);
+const char* moc_last_error(void);
+/* Library version string, e.g. "moc-ffn 0.1 gfx950". */
+const char* moc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOC_H */

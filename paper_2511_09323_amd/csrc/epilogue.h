@@ -1,0 +1,129 @@
+// Epilogue functors shared by the generic and the MFMA GEMM kernels.
+//
+// A GEMM kernel hands over accumulators as groups of four consecutive columns of one row:
+//     epi.store4(m, n0, v)      with n0 % 4 == 0, m < M guaranteed by the caller,
+// and the functor guards the column range itself.  For the MoC layer the GEMM row index m is
+// always a token (or a weight row) and n the other dimension, as noted per functor.
+#pragma once
+#include "common.h"
+
+namespace moc {
+
+template <class T> __device__ __forceinline__ void store_vec4(T* p, const float v[4]);
+template <> __device__ __forceinline__ void store_vec4<float>(float* p, const float v[4]) {
+    *reinterpret_cast<f32x4_t*>(p) = f32x4_t{v[0], v[1], v[2], v[3]};
+}
+template <> __device__ __forceinline__ void store_vec4<bf16_t>(bf16_t* p, const float v[4]) {
+    *reinterpret_cast<u32x2_t*>(p) = u32x2_t{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+}
+
+// C[m, n] = acc, row-major with leading dimension ldc.  Columns n >= N are dropped unless
+// pad_to > N, in which case columns in [N, pad_to) are written as zero (keeps the padding of a
+// later contraction operand clean).
+template <class OutT> struct EpiStore {
+    OutT* C;
+    int64_t ldc;
+    int N;
+    int pad_to;
+    __device__ __forceinline__ void store4(int m, int n0, const float v[4]) const {
+        OutT* row = C + (int64_t)m * ldc;
+        if (n0 + 3 < N && (ldc & 3) == 0) {
+            store_vec4<OutT>(row + n0, v);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int n = n0 + r;
+                if (n < N) Elem<OutT>::store(row + n, v[r]);
+                else if (n < pad_to) Elem<OutT>::store(row + n, 0.0f);
+            }
+        }
+    }
+};
+
+// Dense SwiGLU forward, second GEMM (m = token, n = channel): acc = U.  Reads the stored gate,
+// writes u_save and the dense activation Z = SiLU(G) . U (Eq. FFN-2) padded with zeros to ldz.
+template <class E> struct EpiSwigluAct {
+    const E* g_save;  // [T, F]
+    E* u_save;        // [T, F]
+    E* zd;            // [T, ldz]
+    int F;
+    int64_t ldz;
+    __device__ __forceinline__ void store4(int m, int n0, const float v[4]) const {
+        float z[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int n = n0 + r;
+            z[r] = 0.0f;
+            if (n < F) {
+                float u = Elem<E>::round(v[r]);
+                float g = Elem<E>::load(g_save + (int64_t)m * F + n);
+                Elem<E>::store(u_save + (int64_t)m * F + n, u);
+                z[r] = silu_f32(g) * u;
+            }
+        }
+        if (n0 < ldz) store_vec4<E>(zd + (int64_t)m * ldz + n0, z);
+    }
+};
+
+// Backward, first GEMM (m = token t, n = channel j): acc = dz'[t, j] = dy_t . W_down[j, :]
+// (Eq. bp-1).  On selected channels it recomputes s, z' from the stored g, u and forms du, dg
+// (Eqs. bp-2, bp-3); elsewhere everything is zero.  It writes the dense operands the remaining
+// GEMMs contract over: dg, du as [T, ldf] (for dX) and z', dg, du transposed as [F, ldt] (for the
+// three weight gradients).
+//   MoC:   selection comes from a bit mask maskw[T, nw] (bit j%32 of word j/32) with the number
+//          of selected channels before each word in pref[T, nw]; stored values are [T, K].
+//   dense: every channel is selected and the stored values are [T, F].
+template <class E, bool DENSE> struct EpiBwdPointwise {
+    const uint32_t* maskw;
+    const uint16_t* pref;
+    int nw;
+    const E* gvals;
+    const E* uvals;
+    int K;  // row length of gvals / uvals (F when DENSE)
+    E* dgd;
+    E* dud;  // [T, ldf]
+    E* zt;
+    E* dgt;
+    E* dut;  // [F, ldt]
+    int F;
+    int64_t ldf, ldt;
+    __device__ __forceinline__ void store4(int t, int j0, const float v[4]) const {
+        float z[4], dg[4], du[4];
+        uint32_t bits;
+        int slot;
+        if (DENSE) {
+            bits = 0xFu;
+            slot = j0;
+        } else {
+            int wi = j0 >> 5, sh = j0 & 31;
+            uint32_t w = (wi < nw) ? maskw[(int64_t)t * nw + wi] : 0u;
+            bits = (w >> sh) & 0xFu;
+            slot = (wi < nw ? (int)pref[(int64_t)t * nw + wi] : 0) + __popc(w & ((1u << sh) - 1u));
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            z[r] = dg[r] = du[r] = 0.0f;
+            if (j0 + r < F && ((bits >> r) & 1u)) {
+                float g = Elem<E>::load(gvals + (int64_t)t * K + slot);
+                float u = Elem<E>::load(uvals + (int64_t)t * K + slot);
+                moc_bwd_pointwise(g, u, v[r], z[r], dg[r], du[r]);
+                ++slot;
+            }
+        }
+        if (j0 < ldf) {
+            store_vec4<E>(dgd + (int64_t)t * ldf + j0, dg);
+            store_vec4<E>(dud + (int64_t)t * ldf + j0, du);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int j = j0 + r;
+            if (j < F) {
+                Elem<E>::store(zt + (int64_t)j * ldt + t, z[r]);
+                Elem<E>::store(dgt + (int64_t)j * ldt + t, dg[r]);
+                Elem<E>::store(dut + (int64_t)j * ldt + t, du[r]);
+            }
+        }
+    }
+};
+
+}  // namespace moc

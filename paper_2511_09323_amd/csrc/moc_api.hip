@@ -1,0 +1,614 @@
+// C ABI of the MoC FFN library (see include/moc.h): argument checks, workspace carving and the
+// kernel sequence of every entry point.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/moc.h"
+#include "common.h"
+#include "decode_kernels.h"
+#include "epilogue.h"
+#include "gemm_generic.h"
+#include "gemm_mfma.h"
+#include "misc_kernels.h"
+#include "topk.h"
+
+using namespace moc;
+
+namespace {
+
+// ------------------------------------------------------------------------------- errors
+thread_local char g_err[512] = "";
+
+moc_status fail(moc_status s, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(MOC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---------------------------------------------------------------------- per-kernel timing
+struct TimingEntry {
+    std::string name;
+    double ms = 0.0;
+    int64_t launches = 0;
+};
+struct PendingSpan {
+    int entry;
+    hipEvent_t start, stop;
+};
+bool g_timing_on = false;
+std::vector<TimingEntry> g_entries;
+std::vector<PendingSpan> g_pending;
+std::vector<hipEvent_t> g_event_pool;
+
+hipEvent_t take_event() {
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+int entry_index(const char* name) {
+    for (size_t i = 0; i < g_entries.size(); ++i)
+        if (g_entries[i].name == name) return (int)i;
+    g_entries.push_back(TimingEntry{name, 0.0, 0});
+    return (int)g_entries.size() - 1;
+}
+
+// Brackets the launches made during its lifetime with two events on the stream.
+struct Span {
+    hipStream_t st;
+    hipEvent_t start = nullptr, stop = nullptr;
+    int entry = -1;
+    Span(const char* name, hipStream_t s) : st(s) {
+        if (!g_timing_on) return;
+        start = take_event();
+        stop = take_event();
+        if (!start || !stop) return;
+        entry = entry_index(name);
+        hipEventRecord(start, st);
+    }
+    ~Span() {
+        if (entry < 0) return;
+        hipEventRecord(stop, st);
+        g_pending.push_back(PendingSpan{entry, start, stop});
+    }
+};
+
+// ------------------------------------------------------------------------ small helpers
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+struct Carver {   // hands out 256-byte aligned pieces of the workspace
+    unsigned char* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    template <class T> T* take(size_t count) {
+        T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += round_up_sz(count * sizeof(T), 256);
+        return r;
+    }
+};
+
+int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+struct Options {
+    int force_generic;   // MOC_FORCE_GENERIC=1: never use the MFMA GEMM
+    int tile;            // MOC_GEMM_TILE=256|128|0 (0 = choose by problem size)
+    Options() : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)) {}
+};
+const Options& options() {
+    static Options o;
+    return o;
+}
+
+moc_status check_shape(const moc_shape* s, bool decode) {
+    if (!s) return fail(MOC_ERR_BAD_ARG, "shape is NULL");
+    if (s->dtype != MOC_F32 && s->dtype != MOC_BF16) return fail(MOC_ERR_BAD_ARG, "unknown dtype %d", s->dtype);
+    if (s->T < 1 || s->d < 1 || s->F < 1) return fail(MOC_ERR_BAD_ARG, "T, d, F must be >= 1 (got %d, %d, %d)", s->T, s->d, s->F);
+    if (s->K < 1 || s->K > s->F) return fail(MOC_ERR_BAD_ARG, "K must satisfy 1 <= K <= F (got K=%d, F=%d)", s->K, s->F);
+    if (s->F > 32768) return fail(MOC_ERR_UNSUPPORTED, "F = %d exceeds 32768", s->F);
+    if (s->dtype == MOC_BF16 && s->d % 8 != 0) return fail(MOC_ERR_BAD_ARG, "bf16 needs d %% 8 == 0 (got %d)", s->d);
+    if (s->dtype == MOC_F32 && s->d % 4 != 0 && decode) return fail(MOC_ERR_BAD_ARG, "fp32 decode needs d %% 4 == 0 (got %d)", s->d);
+    if ((int64_t)s->T * s->F >= (1ll << 40)) return fail(MOC_ERR_UNSUPPORTED, "T*F too large");
+    if (decode && s->T > 16) return fail(MOC_ERR_BAD_ARG, "decode batch must be <= 16 (got %d)", s->T);
+    return MOC_OK;
+}
+
+#define CHECK_PTR(p)                                                                   \
+    do {                                                                               \
+        if ((p) == nullptr) return fail(MOC_ERR_BAD_ARG, "%s is NULL", #p);            \
+        if (!aligned16(p)) return fail(MOC_ERR_BAD_ARG, "%s is not 16-byte aligned", #p); \
+    } while (0)
+
+// ------------------------------------------------------------------------ GEMM dispatch
+template <class E, class Epi>
+moc_status run_gemm(const char* name, const GemmOperands<E>& op, int M, int N, const Epi& epi, hipStream_t st) {
+    Span span(name, st);
+    if constexpr (std::is_same<E, bf16_t>::value) {
+        if (!options().force_generic && mfma_operands_ok(op)) {
+            int tile = options().tile;
+            if (tile == 0) {
+                const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
+                tile = t256 >= 192 ? 256 : 128;
+            }
+            hipError_t e = tile == 256 ? launch_gemm_nt_bf16_mfma_cfg<256, 256, 64, 2, 2>(op, M, N, epi, st)
+                                       : launch_gemm_nt_bf16_mfma_cfg<128, 128, 64, 2, 2>(op, M, N, epi, st);
+            if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+            return MOC_OK;
+        }
+    }
+    launch_gemm_nt_generic<E, Epi>(op, M, N, epi, st);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E>
+GemmOperands<E> operands(const E* A, int64_t lda, const E* B, int64_t ldb, int Kc, const E* A2 = nullptr,
+                         const E* B2 = nullptr, int Kc2 = 0) {
+    return GemmOperands<E>{A, B, lda, ldb, Kc, A2, B2, lda, ldb, Kc2};
+}
+
+template <class E>
+moc_status run_transpose(const char* name, const E* in, int64_t ld_in, int R, int C, E* out, int64_t ld_out,
+                         hipStream_t st) {
+    Span span(name, st);
+    dim3 grid((unsigned)((ld_out + 63) / 64), (unsigned)((C + 63) / 64));
+    hipLaunchKernelGGL((transpose_pad_kernel<E>), grid, dim3(256), 0, st, in, ld_in, R, C, out, ld_out);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E, int NT, int VEC, bool FUSED>
+moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
+    const size_t lds = topk_lds_bytes(a.F, NT, VEC);
+    if (lds > 160 * 1024 - 64) return fail(MOC_ERR_UNSUPPORTED, "F = %d needs %zu bytes of LDS for Top-K", a.F, lds);
+    auto kern = topk_rows_kernel<E, NT, VEC, FUSED>;
+    static size_t attr_bytes = 0;
+    if (lds > attr_bytes) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - 64));
+        attr_bytes = 160 * 1024 - 64;
+    }
+    Span span(name, st);
+    hipLaunchKernelGGL(kern, dim3(T), dim3(NT), lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+// ------------------------------------------------------------------- workspace layouts
+struct Dims {
+    int T, d, F, K;
+    int ldF, ldT, nw;
+    explicit Dims(const moc_shape& s) : T(s.T), d(s.d), F(s.F), K(s.K) {
+        ldF = round_up(F, 64);
+        ldT = round_up(T, 64);
+        nw = ldF / 32;
+    }
+};
+
+template <class E> struct FwdWs {
+    float* G;
+    E *U, *Zd, *WdT;
+    size_t bytes;
+    FwdWs(void* ws, const Dims& D, bool dense) {
+        Carver c(ws);
+        G = dense ? nullptr : c.take<float>((size_t)D.T * D.ldF);
+        U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
+        Zd = c.take<E>((size_t)D.T * D.ldF);
+        WdT = c.take<E>((size_t)D.d * D.ldF);
+        bytes = c.off;
+    }
+};
+
+template <class E> struct BwdWs {
+    uint32_t* maskw;
+    uint16_t* pref;
+    E *dGd, *dUd, *ZT, *dGT, *dUT, *XT, *dYT, *WgT, *WuT;
+    size_t bytes;
+    BwdWs(void* ws, const Dims& D, bool dense) {
+        Carver c(ws);
+        maskw = dense ? nullptr : c.take<uint32_t>((size_t)D.T * D.nw);
+        pref = dense ? nullptr : c.take<uint16_t>((size_t)D.T * D.nw);
+        dGd = c.take<E>((size_t)D.T * D.ldF);
+        dUd = c.take<E>((size_t)D.T * D.ldF);
+        ZT = c.take<E>((size_t)D.F * D.ldT);
+        dGT = c.take<E>((size_t)D.F * D.ldT);
+        dUT = c.take<E>((size_t)D.F * D.ldT);
+        XT = c.take<E>((size_t)D.d * D.ldT);
+        dYT = c.take<E>((size_t)D.d * D.ldT);
+        WgT = c.take<E>((size_t)D.d * D.ldF);
+        WuT = c.take<E>((size_t)D.d * D.ldF);
+        bytes = c.off;
+    }
+};
+
+int decode_splits(int B) {
+    int P = 128 / B;
+    return P < 8 ? 8 : (P > 64 ? 64 : P);
+}
+
+struct DecodeWs {
+    float *g, *gsel, *z, *part;
+    int32_t* idx;
+    size_t bytes;
+    DecodeWs(void* ws, const Dims& D) {
+        Carver c(ws);
+        g = c.take<float>((size_t)D.T * D.ldF);
+        gsel = c.take<float>((size_t)D.T * D.K);
+        z = c.take<float>((size_t)D.T * D.K);
+        idx = c.take<int32_t>((size_t)D.T * D.K);
+        part = c.take<float>((size_t)decode_splits(D.T) * D.T * D.d);
+        bytes = c.off;
+    }
+};
+
+template <class E> size_t workspace_for(const Dims& D, int op) {
+    switch (op) {
+        case MOC_OP_FWD: return FwdWs<E>(nullptr, D, false).bytes;
+        case MOC_OP_BWD: return BwdWs<E>(nullptr, D, false).bytes;
+        case MOC_OP_DECODE: return DecodeWs(nullptr, D).bytes;
+        case MOC_OP_SWIGLU_FWD: return FwdWs<E>(nullptr, D, true).bytes;
+        case MOC_OP_SWIGLU_BWD: return BwdWs<E>(nullptr, D, true).bytes;
+    }
+    return 0;
+}
+
+// ----------------------------------------------------------------------------- forward
+template <class E>
+moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx, E* gvals,
+                    E* uvals, void* ws, hipStream_t st) {
+    FwdWs<E> W(ws, D, false);
+    moc_status s;
+    if ((s = run_transpose<E>("transpose_wd", wd, D.d, D.F, D.d, W.WdT, D.ldF, st)) != MOC_OK) return s;
+    // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
+    if ((s = run_gemm<E>("gemm_gate", operands<E>(x, D.d, wg, D.d, D.d), D.T, D.F,
+                         EpiStore<float>{W.G, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
+    // U = X W_up (Eq. MoC-1)
+    if ((s = run_gemm<E>("gemm_up", operands<E>(x, D.d, wu, D.d, D.d), D.T, D.F, EpiStore<E>{W.U, D.ldF, D.F, 0},
+                         st)) != MOC_OK) return s;
+    // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
+    TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
+    if ((s = run_topk<E, 256, 4, true>("topk_select_act", a, D.T, st)) != MOC_OK) return s;
+    // D = Z' W_down (Eq. MoC-2)
+    return run_gemm<E>("gemm_down", operands<E>(W.Zd, D.ldF, W.WdT, D.ldF, D.ldF), D.T, D.d,
+                       EpiStore<E>{y, D.d, D.d, 0}, st);
+}
+
+// ---------------------------------------------------------------------------- backward
+template <class E, bool DENSE>
+moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, const int32_t* idx,
+                    const E* gvals, const E* uvals, const E* dy, E* dx, E* dwg, E* dwu, E* dwd, void* ws,
+                    hipStream_t st) {
+    BwdWs<E> W(ws, D, DENSE);
+    moc_status s;
+    if (!DENSE) {
+        Span span("build_mask", st);
+        hipLaunchKernelGGL(build_mask_kernel, dim3(D.T), dim3(256), (size_t)D.nw * 4 + 16, st, idx, D.K, D.F, D.nw,
+                           W.maskw, W.pref);
+        HIP_TRY(hipGetLastError());
+    }
+    if ((s = run_transpose<E>("transpose_x", x, D.d, D.T, D.d, W.XT, D.ldT, st)) != MOC_OK) return s;
+    if ((s = run_transpose<E>("transpose_dy", dy, D.d, D.T, D.d, W.dYT, D.ldT, st)) != MOC_OK) return s;
+    if ((s = run_transpose<E>("transpose_wg", wg, D.d, D.F, D.d, W.WgT, D.ldF, st)) != MOC_OK) return s;
+    if ((s = run_transpose<E>("transpose_wu", wu, D.d, D.F, D.d, W.WuT, D.ldF, st)) != MOC_OK) return s;
+    if (D.ldT > D.T) {
+        Span span("zero_pad", st);
+        hipLaunchKernelGGL((zero_cols_kernel<E>), dim3(256), dim3(256), 0, st, W.ZT, W.dGT, W.dUT, D.F, D.T,
+                           (int64_t)D.ldT);
+        HIP_TRY(hipGetLastError());
+    }
+    // dZ' = dD W_down^T (bp-1) with the pointwise part (bp-2, bp-3) in the epilogue
+    EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.dGd, W.dUd,
+                                  W.ZT,    W.dGT,  W.dUT, D.F,  D.ldF, D.ldT};
+    if ((s = run_gemm<E>("gemm_dz_pointwise", operands<E>(dy, D.d, wd, D.d, D.d), D.T, D.F, epi, st)) != MOC_OK)
+        return s;
+    // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens
+    if ((s = run_gemm<E>("gemm_dwd", operands<E>(W.ZT, D.ldT, W.dYT, D.ldT, D.ldT), D.F, D.d,
+                         EpiStore<E>{dwd, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    if ((s = run_gemm<E>("gemm_dwg", operands<E>(W.dGT, D.ldT, W.XT, D.ldT, D.ldT), D.F, D.d,
+                         EpiStore<E>{dwg, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    if ((s = run_gemm<E>("gemm_dwu", operands<E>(W.dUT, D.ldT, W.XT, D.ldT, D.ldT), D.F, D.d,
+                         EpiStore<E>{dwu, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
+    return run_gemm<E>("gemm_dx", operands<E>(W.dGd, D.ldF, W.WgT, D.ldF, D.ldF, W.dUd, W.WuT, D.ldF), D.T, D.d,
+                       EpiStore<E>{dx, D.d, D.d, 0}, st);
+}
+
+// ------------------------------------------------------------------------ dense SwiGLU
+template <class E>
+moc_status swiglu_fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, E* g_save,
+                           E* u_save, void* ws, hipStream_t st) {
+    FwdWs<E> W(ws, D, true);
+    moc_status s;
+    if ((s = run_transpose<E>("transpose_wd", wd, D.d, D.F, D.d, W.WdT, D.ldF, st)) != MOC_OK) return s;
+    if ((s = run_gemm<E>("gemm_gate_dense", operands<E>(x, D.d, wg, D.d, D.d), D.T, D.F,
+                         EpiStore<E>{g_save, D.F, D.F, 0}, st)) != MOC_OK) return s;
+    if ((s = run_gemm<E>("gemm_up_act_dense", operands<E>(x, D.d, wu, D.d, D.d), D.T, D.F,
+                         EpiSwigluAct<E>{g_save, u_save, W.Zd, D.F, D.ldF}, st)) != MOC_OK) return s;
+    return run_gemm<E>("gemm_down", operands<E>(W.Zd, D.ldF, W.WdT, D.ldF, D.ldF), D.T, D.d,
+                       EpiStore<E>{y, D.d, D.d, 0}, st);
+}
+
+// ------------------------------------------------------------------------------ decode
+template <class E, int BT>
+moc_status decode_gate(const Dims& D, const E* x, const E* wg, float* g, hipStream_t st) {
+    const size_t lds = (size_t)BT * D.d * sizeof(E);
+    if (lds > 160 * 1024 - 64) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large for LDS staging", D.d);
+    auto kern = decode_gate_kernel<E, BT>;
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - 64));
+        attr = true;
+    }
+    Span span("decode_gate", st);
+    const int per_cu = lds > 80 * 1024 ? 1 : (lds > 40 * 1024 ? 2 : 4);
+    const int grid = std::min((D.F + 3) / 4, 256 * per_cu);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, x, wg, D.T, D.d, D.F, g, (int64_t)D.ldF);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E>
+moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx_out,
+                       void* ws, hipStream_t st) {
+    DecodeWs W(ws, D);
+    const int B = D.T;
+    int32_t* idx = idx_out ? idx_out : W.idx;
+    moc_status s;
+    if (B == 1) s = decode_gate<E, 1>(D, x, wg, W.g, st);
+    else if (B <= 4) s = decode_gate<E, 4>(D, x, wg, W.g, st);
+    else s = decode_gate<E, 16>(D, x, wg, W.g, st);
+    if (s != MOC_OK) return s;
+    TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+    if ((s = run_topk<float, 1024, 4, false>("decode_topk", a, B, st)) != MOC_OK) return s;
+    {
+        const size_t lds = (size_t)D.d * sizeof(E);
+        if (lds > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
+        Span span("decode_up", st);
+        const int gx = std::max(1, std::min((D.K + 3) / 4, 1024 / B));
+        hipLaunchKernelGGL((decode_up_kernel<E>), dim3(gx, B), dim3(256), lds, st, x, wu, idx, W.gsel, D.d, D.K, W.z);
+        HIP_TRY(hipGetLastError());
+    }
+    const int P = decode_splits(B);
+    {
+        Span span("decode_down", st);
+        constexpr int SLICE = 64 * Chunk<E>::N * 4;
+        hipLaunchKernelGGL((decode_down_kernel<E, 4>), dim3(P, B, (D.d + SLICE - 1) / SLICE), dim3(256), 0, st, wd, idx,
+                           W.z, D.d, D.K, P, W.part);
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        Span span("decode_reduce", st);
+        const int64_t n = (int64_t)B * D.d;
+        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, W.part, P, n,
+                           y);
+        HIP_TRY(hipGetLastError());
+    }
+    return MOC_OK;
+}
+
+}  // namespace
+
+// =============================================================================== C ABI
+extern "C" {
+
+size_t moc_workspace_bytes(const moc_shape* shape, int op) {
+    if (check_shape(shape, op == MOC_OP_DECODE) != MOC_OK) return 0;
+    if (op < MOC_OP_FWD || op > MOC_OP_SWIGLU_BWD) return 0;
+    Dims D(*shape);
+    return shape->dtype == MOC_BF16 ? workspace_for<bf16_t>(D, op) : workspace_for<float>(D, op);
+}
+
+#define CHECK_WS(op)                                                                                  \
+    do {                                                                                              \
+        CHECK_PTR(ws);                                                                                \
+        size_t need_ = moc_workspace_bytes(shape, op);                                                \
+        if (ws_bytes < need_) return fail(MOC_ERR_WORKSPACE, "workspace: %zu bytes given, %zu needed", ws_bytes, need_); \
+    } while (0)
+
+moc_status moc_ffn_fwd(const moc_shape* shape, const void* x, const void* wg, const void* wu, const void* wd, void* y,
+                       int32_t* idx, void* gvals, void* uvals, void* ws, size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_WS(MOC_OP_FWD);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return fwd_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd, (bf16_t*)y,
+                                idx, (bf16_t*)gvals, (bf16_t*)uvals, ws, st);
+    return fwd_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y, idx,
+                           (float*)gvals, (float*)uvals, ws, st);
+}
+
+moc_status moc_ffn_bwd(const moc_shape* shape, const void* x, const void* wg, const void* wu, const void* wd,
+                       const int32_t* idx, const void* gvals, const void* uvals, const void* dy, void* dx, void* dwg,
+                       void* dwu, void* dwd, void* ws, size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_PTR(dy); CHECK_PTR(dx); CHECK_PTR(dwg); CHECK_PTR(dwu); CHECK_PTR(dwd);
+    CHECK_WS(MOC_OP_BWD);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return bwd_impl<bf16_t, false>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd, idx,
+                                       (const bf16_t*)gvals, (const bf16_t*)uvals, (const bf16_t*)dy, (bf16_t*)dx,
+                                       (bf16_t*)dwg, (bf16_t*)dwu, (bf16_t*)dwd, ws, st);
+    return bwd_impl<float, false>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, idx,
+                                  (const float*)gvals, (const float*)uvals, (const float*)dy, (float*)dx, (float*)dwg,
+                                  (float*)dwu, (float*)dwd, ws, st);
+}
+
+moc_status moc_ffn_decode(const moc_shape* shape, const void* x, const void* wg, const void* wu, const void* wd,
+                          void* y, int32_t* idx_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, true);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y);
+    if (idx_or_null && !aligned16(idx_or_null)) return fail(MOC_ERR_BAD_ARG, "idx is not 16-byte aligned");
+    CHECK_WS(MOC_OP_DECODE);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return decode_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                   (bf16_t*)y, idx_or_null, ws, st);
+    return decode_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y,
+                              idx_or_null, ws, st);
+}
+
+moc_status moc_swiglu_fwd(const moc_shape* shape_in, const void* x, const void* wg, const void* wu, const void* wd,
+                          void* y, void* g_save, void* u_save, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!shape_in) return fail(MOC_ERR_BAD_ARG, "shape is NULL");
+    moc_shape sh = *shape_in;
+    sh.K = sh.F;
+    const moc_shape* shape = &sh;
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y); CHECK_PTR(g_save); CHECK_PTR(u_save);
+    CHECK_WS(MOC_OP_SWIGLU_FWD);
+    Dims D(sh);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (sh.dtype == MOC_BF16)
+        return swiglu_fwd_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                       (bf16_t*)y, (bf16_t*)g_save, (bf16_t*)u_save, ws, st);
+    return swiglu_fwd_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y,
+                                  (float*)g_save, (float*)u_save, ws, st);
+}
+
+moc_status moc_swiglu_bwd(const moc_shape* shape_in, const void* x, const void* wg, const void* wu, const void* wd,
+                          const void* g_save, const void* u_save, const void* dy, void* dx, void* dwg, void* dwu,
+                          void* dwd, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!shape_in) return fail(MOC_ERR_BAD_ARG, "shape is NULL");
+    moc_shape sh = *shape_in;
+    sh.K = sh.F;
+    const moc_shape* shape = &sh;
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(g_save); CHECK_PTR(u_save);
+    CHECK_PTR(dy); CHECK_PTR(dx); CHECK_PTR(dwg); CHECK_PTR(dwu); CHECK_PTR(dwd);
+    CHECK_WS(MOC_OP_SWIGLU_BWD);
+    Dims D(sh);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (sh.dtype == MOC_BF16)
+        return bwd_impl<bf16_t, true>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                      nullptr, (const bf16_t*)g_save, (const bf16_t*)u_save, (const bf16_t*)dy,
+                                      (bf16_t*)dx, (bf16_t*)dwg, (bf16_t*)dwu, (bf16_t*)dwd, ws, st);
+    return bwd_impl<float, true>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, nullptr,
+                                 (const float*)g_save, (const float*)u_save, (const float*)dy, (float*)dx, (float*)dwg,
+                                 (float*)dwu, (float*)dwd, ws, st);
+}
+
+moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_t ldg, int32_t* idx, float* gsel,
+                         void* hip_stream) {
+    if (T < 1 || F < 1 || K < 1 || K > F) return fail(MOC_ERR_BAD_ARG, "need T >= 1 and 1 <= K <= F (T=%d F=%d K=%d)", T, F, K);
+    if (F > 32768) return fail(MOC_ERR_UNSUPPORTED, "F = %d exceeds 32768", F);
+    if (ldg < F) return fail(MOC_ERR_BAD_ARG, "ldg < F");
+    CHECK_PTR(g); CHECK_PTR(idx); CHECK_PTR(gsel);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    TopkArgs<float> a{g, ldg, F, K, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+    if (ldg % 4 == 0) return run_topk<float, 256, 4, false>("topk_rows", a, T, st);
+    return run_topk<float, 256, 1, false>("topk_rows", a, T, st);
+}
+
+moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain, float eps, void* out,
+                       void* hip_stream) {
+    if (T < 1 || d < 1) return fail(MOC_ERR_BAD_ARG, "T and d must be >= 1");
+    if (dtype != MOC_F32 && dtype != MOC_BF16) return fail(MOC_ERR_BAD_ARG, "unknown dtype %d", dtype);
+    CHECK_PTR(h); CHECK_PTR(gain); CHECK_PTR(out);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Span span("rmsnorm", st);
+    if (dtype == MOC_BF16)
+        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t>), dim3(T), dim3(256), 0, st, (const bf16_t*)h, (const bf16_t*)gain, eps, d, (bf16_t*)out);
+    else
+        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(T), dim3(256), 0, st, (const float*)h, (const float*)gain, eps, d, (float*)out);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+moc_status moc_residual_add(int32_t T, int32_t d, int32_t dtype, void* h_inout, const void* y, void* hip_stream) {
+    if (T < 1 || d < 1) return fail(MOC_ERR_BAD_ARG, "T and d must be >= 1");
+    if (dtype != MOC_F32 && dtype != MOC_BF16) return fail(MOC_ERR_BAD_ARG, "unknown dtype %d", dtype);
+    CHECK_PTR(h_inout); CHECK_PTR(y);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Span span("residual_add", st);
+    const int64_t n = (int64_t)T * d;
+    const unsigned grid = (unsigned)std::min<int64_t>((n + 255) / 256, 65536);
+    if (dtype == MOC_BF16)
+        hipLaunchKernelGGL((residual_add_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, (bf16_t*)h_inout, (const bf16_t*)y, n);
+    else
+        hipLaunchKernelGGL((residual_add_kernel<float>), dim3(grid), dim3(256), 0, st, (float*)h_inout, (const float*)y, n);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+void moc_timing_enable(int on) { g_timing_on = on != 0; }
+
+int32_t moc_timing_collect(void) {
+    for (const PendingSpan& p : g_pending) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(p.stop) == hipSuccess && hipEventElapsedTime(&ms, p.start, p.stop) == hipSuccess) {
+            g_entries[p.entry].ms += ms;
+            g_entries[p.entry].launches += 1;
+        }
+        g_event_pool.push_back(p.start);
+        g_event_pool.push_back(p.stop);
+    }
+    g_pending.clear();
+    return (int32_t)g_entries.size();
+}
+
+moc_status moc_timing_get(int32_t i, char* name, int32_t name_cap, double* total_ms, int64_t* launches) {
+    if (i < 0 || i >= (int32_t)g_entries.size()) return fail(MOC_ERR_BAD_ARG, "timing entry %d out of range", i);
+    if (name && name_cap > 0) {
+        strncpy(name, g_entries[i].name.c_str(), name_cap - 1);
+        name[name_cap - 1] = 0;
+    }
+    if (total_ms) *total_ms = g_entries[i].ms;
+    if (launches) *launches = g_entries[i].launches;
+    return MOC_OK;
+}
+
+void moc_timing_reset(void) {
+    moc_timing_collect();
+    g_entries.clear();
+}
+
+const char* moc_status_string(int status) {
+    switch (status) {
+        case MOC_OK: return "MOC_OK";
+        case MOC_ERR_BAD_ARG: return "MOC_ERR_BAD_ARG";
+        case MOC_ERR_WORKSPACE: return "MOC_ERR_WORKSPACE";
+        case MOC_ERR_UNSUPPORTED: return "MOC_ERR_UNSUPPORTED";
+        case MOC_ERR_HIP: return "MOC_ERR_HIP";
+    }
+    return "MOC_ERR_UNKNOWN";
+}
+
+const char* moc_last_error(void) { return g_err; }
+
+const char* moc_version(void) { return "moc-ffn 0.1 gfx950"; }
+
+}  // extern "C"

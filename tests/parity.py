@@ -1,0 +1,87 @@
+"""Helpers shared by the GPU parity tests: moving seeded inputs to the device, calling the CPU
+oracle in the paper's layout, and the comparison rules (max-norm relative error; index sets
+bit-exact except inside the near-tie window of the fp32 gate)."""
+import numpy as np
+import torch
+
+from oracle import moc_oracle as O
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+TIE_WINDOW = 1e-6
+
+
+def to_dev(a, dtype):
+    """float32 numpy array (bf16-exact when dtype is bf16) -> GPU tensor of that dtype, exactly."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda").to(TORCH_DTYPE[dtype]).contiguous()
+
+
+def to_np(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def paper_weights(L):
+    """Channel-major [F, d] arrays -> the paper's W_gate [d,F], W_up [d,F], W_down [F,d] in float64."""
+    return (L["wg"].astype(np.float64).T, L["wu"].astype(np.float64).T, L["wd"].astype(np.float64))
+
+
+def maxrel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.max(np.abs(b))
+    return float(np.max(np.abs(a - b)) / (den if den > 0 else 1.0))
+
+
+def assert_close(name, got, want, tol):
+    err = maxrel(got, want)
+    assert err <= tol, "%s: max-norm relative error %.3e > %.1e" % (name, err, tol)
+    return err
+
+
+def check_index_sets(idx_gpu, G64, K):
+    """idx_gpu [T,K] int; G64 the oracle's float64 gate [T,F].  Every row must be strictly
+    ascending, in range, and equal to the oracle's set -- unless the row's K-th / (K+1)-th fp32 gate
+    values are within the 1e-6 relative window, in which case any set that keeps everything
+    clearly above the threshold and nothing clearly below it is accepted.  Returns the rows that
+    needed the window."""
+    idx_gpu = np.asarray(idx_gpu)
+    T, F = G64.shape
+    assert idx_gpu.shape == (T, K)
+    assert np.all(idx_gpu >= 0) and np.all(idx_gpu < F)
+    if K > 1:
+        assert np.all(np.diff(idx_gpu, axis=1) > 0), "idx rows must ascend strictly"
+    M_ref = O.topk_mask(G64, K)
+    M_gpu = O.mask_from_idx(idx_gpu, F)
+    differing = np.flatnonzero((M_ref != M_gpu).any(axis=1))
+    g32 = G64.astype(np.float32)
+    for t in differing:
+        row = g32[t].astype(np.float64)
+        tau = np.sort(row)[F - K]
+        tol = TIE_WINDOW * max(abs(tau), 1e-30)
+        must = row > tau + tol
+        never = row < tau - tol
+        assert np.all(M_gpu[t][must]), "row %d drops a channel clearly above the threshold" % t
+        assert not np.any(M_gpu[t][never]), "row %d keeps a channel clearly below the threshold" % t
+    return differing
+
+
+def oracle_forward_for(L, idx_gpu):
+    """Oracle outputs for the GPU's own index sets: (D, gvals, uvals, G) in float64."""
+    Wg, Wu, Wd = paper_weights(L)
+    X = L["x"].astype(np.float64)
+    F = Wg.shape[1]
+    M = O.mask_from_idx(np.asarray(idx_gpu), F)
+    D, G, U = O.moc_forward_given_mask(X, Wg, Wu, Wd, M)
+    rows = np.arange(X.shape[0])[:, None]
+    return D, G[rows, idx_gpu], U[rows, idx_gpu], G
+
+
+def oracle_backward_for(L, idx, gvals, uvals):
+    """Oracle gradients from the stored set exactly as the GPU stored it; weight gradients are
+    returned channel-major [F, d] like the library's."""
+    Wg, Wu, Wd = paper_weights(L)
+    X = L["x"].astype(np.float64)
+    F = Wg.shape[1]
+    M, GM, UM = O.expand_saved(idx, gvals, uvals, F)
+    dX, dWg, dWu, dWd = O.moc_backward(X, Wg, Wu, Wd, M, GM, UM, L["dy"].astype(np.float64))
+    return dX, dWg.T, dWu.T, dWd
