@@ -67,9 +67,9 @@ template <class E> struct EpiSwigluAct {
 
 // Backward, first GEMM (m = token t, n = channel j): acc = dz'[t, j] = dy_t . W_down[j, :]
 // (Eq. bp-1).  On selected channels it recomputes s, z' from the stored g, u and forms du, dg
-// (Eqs. bp-2, bp-3); elsewhere everything is zero.  It writes the dense operands the remaining
-// GEMMs contract over: dg, du as [T, ldf] (for dX) and z', dg, du transposed as [F, ldt] (for the
-// three weight gradients).
+// (Eqs. bp-2, bp-3); elsewhere everything is zero.  It writes the dense [T, ldf] operands the
+// remaining GEMMs contract over: z' (for dW_down), dg and du (for dW_gate, dW_up and dX), zero on
+// unselected channels and on the padding columns [F, ldf).
 //   MoC:   selection comes from a bit mask maskw[T, nw] (bit j%32 of word j/32) with the number
 //          of selected channels before each word in pref[T, nw]; stored values are [T, K].
 //   dense: every channel is selected and the stored values are [T, F].
@@ -80,14 +80,13 @@ template <class E, bool DENSE> struct EpiBwdPointwise {
     const E* gvals;
     const E* uvals;
     int K;  // row length of gvals / uvals (F when DENSE)
+    E* zd;
     E* dgd;
     E* dud;  // [T, ldf]
-    E* zt;
-    E* dgt;
-    E* dut;  // [F, ldt]
     int F;
-    int64_t ldf, ldt;
+    int64_t ldf;
     __device__ __forceinline__ void store4(int t, int j0, const float v[4]) const {
+        if (j0 >= ldf) return;
         float z[4], dg[4], du[4];
         uint32_t bits;
         int slot;
@@ -95,34 +94,24 @@ template <class E, bool DENSE> struct EpiBwdPointwise {
             bits = 0xFu;
             slot = j0;
         } else {
-            int wi = j0 >> 5, sh = j0 & 31;
-            uint32_t w = (wi < nw) ? maskw[(int64_t)t * nw + wi] : 0u;
+            const int wi = j0 >> 5, sh = j0 & 31;
+            const uint32_t w = maskw[(int64_t)t * nw + wi];
             bits = (w >> sh) & 0xFu;
-            slot = (wi < nw ? (int)pref[(int64_t)t * nw + wi] : 0) + __popc(w & ((1u << sh) - 1u));
+            slot = (int)pref[(int64_t)t * nw + wi] + __popc(w & ((1u << sh) - 1u));
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             z[r] = dg[r] = du[r] = 0.0f;
             if (j0 + r < F && ((bits >> r) & 1u)) {
-                float g = Elem<E>::load(gvals + (int64_t)t * K + slot);
-                float u = Elem<E>::load(uvals + (int64_t)t * K + slot);
+                const float g = Elem<E>::load(gvals + (int64_t)t * K + slot);
+                const float u = Elem<E>::load(uvals + (int64_t)t * K + slot);
                 moc_bwd_pointwise(g, u, v[r], z[r], dg[r], du[r]);
                 ++slot;
             }
         }
-        if (j0 < ldf) {
-            store_vec4<E>(dgd + (int64_t)t * ldf + j0, dg);
-            store_vec4<E>(dud + (int64_t)t * ldf + j0, du);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            int j = j0 + r;
-            if (j < F) {
-                Elem<E>::store(zt + (int64_t)j * ldt + t, z[r]);
-                Elem<E>::store(dgt + (int64_t)j * ldt + t, dg[r]);
-                Elem<E>::store(dut + (int64_t)j * ldt + t, du[r]);
-            }
-        }
+        store_vec4<E>(zd + (int64_t)t * ldf + j0, z);
+        store_vec4<E>(dgd + (int64_t)t * ldf + j0, dg);
+        store_vec4<E>(dud + (int64_t)t * ldf + j0, du);
     }
 };
 

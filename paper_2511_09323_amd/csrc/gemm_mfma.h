@@ -1,42 +1,111 @@
 // bf16 x bf16 -> fp32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16).
 //
-//   C[m, n] = sum_k A[m, k] B[n, k]  (+ a second operand pair accumulated into the same tile)
+//   C[m, n] = sum_k A(m, k) B(n, k)   (+ a second operand pair accumulated into the same tile)
 //
-// Both operands are row-major with the contraction index contiguous, every contraction length is
-// a multiple of BK and every leading dimension a multiple of 8 elements (the host checks this).
-// One workgroup computes a BM x BN tile; its WGM x WGN wavefronts each own a (BM/WGM) x (BN/WGN)
-// sub-tile made of 32x32 MFMA blocks.  k-slices of BK elements are staged global -> registers ->
-// LDS, two LDS stages, one barrier per slice.  LDS rows are padded by 16 bytes so that the
-// 16-byte fragment reads of 16 consecutive rows fall on disjoint banks.
+// Each operand is read in the layout it already has in memory:
+//   k-contiguous ("KC"): element (r, k) at P[r * ld + k]   -- x, dy, the weights for X W^T products
+//   k-major      ("KM"): element (r, k) at P[k * ld + r]   -- the same arrays when the contraction
+//                                                             runs over their row index
+// so no transposed copies are ever made.  KC tiles are staged in LDS as [row][k] and fragments are
+// plain 16-byte reads; KM tiles are staged as [k][row] exactly as they lie in memory and fragments
+// come from two ds_read_b64_tr_b16 transposing reads (each gives a lane 4 consecutive k of one row).
+//
+// One 256-thread workgroup computes a BM x BN tile; its 2 x 2 wavefronts each own a
+// (BM/2) x (BN/2) sub-tile of 32x32 MFMA blocks.  k-slices of 32 are staged global -> registers
+// -> LDS through three LDS stages: while slice t is multiplied, slice t+1 is already visible in
+// LDS, slice t+2 is being written and slices t+3, t+4 are in flight from global memory.  One barrier per
+// slice.  Fragment registers are double-buffered so LDS reads overlap the MFMAs of the previous
+// half-slice; sched_group_barrier pins that interleaving.
 //
 // Operand roles: the B rows (n) feed the MFMA "A" input and the A rows (m) the MFMA "B" input, so
-// a lane ends up with four consecutive n for one m -- the shape the epilogues want for
-// row-major [m, n] stores.
+// a lane ends up with four consecutive n for one m -- the shape the epilogues want.
+//
+// Requirements checked by the host: 16-byte aligned bases, leading dimensions multiples of 8,
+// contraction lengths >= 32; a KC operand must be readable up to the next multiple of 8 past the
+// contraction length and hold zeros there (or meet zeros of the other operand); a KM operand must
+// be readable up to `ext` columns (multiple of 8).  Contraction tails (length % 32 != 0) use the
+// KTAIL instantiation: the last slice re-reads the final 32-wide window (8-aligned) and zeroes
+// what lies before the part still to be accumulated or past the end; k-major rows past the end
+// are clamped to the last row before being zeroed.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_generic.h"
 
 namespace moc {
 
-template <int BM, int BN, int BK, int WGM, int WGN> struct MfmaCfg {
-    static constexpr int kThreads = WGM * WGN * 64;
-    static constexpr int kPitch = BK * 2 + 16;                 // bytes per LDS row
-    static constexpr int kStage = (BM + BN) * kPitch;          // bytes per stage
-    static constexpr int kLds = 2 * kStage;
+typedef GemmProblem<bf16_t> MfmaProblem;
+
+constexpr int kMfmaBK = 32;
+constexpr int kMfmaStages = 3;
+
+template <int ROWS, bool KM> struct OperandTile {
+    static constexpr int kPitch = KM ? (ROWS * 2 + 64) : (kMfmaBK * 2 + 16);   // bytes
+    static constexpr int kBytes = KM ? kMfmaBK * kPitch : ROWS * kPitch;
+    static constexpr int kChunks = ROWS * kMfmaBK / 8 / 256;                    // 16-byte chunks per thread
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_bf16_mfma_kernel(GemmOperands<bf16_t> op, int M, int N,
-                                                                            int tiles_m, int tiles_n, Epi epi) {
-    using Cfg = MfmaCfg<BM, BN, BK, WGM, WGN>;
-    constexpr int NTHR = Cfg::kThreads;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
+template <int BM, int BN, bool AKM, bool BKM> struct MfmaCfg {
+    using TA = OperandTile<BM, AKM>;
+    using TB = OperandTile<BN, BKM>;
+    static constexpr int kStage = TA::kBytes + TB::kBytes;
+    static constexpr int kLds = kMfmaStages * kStage;
+};
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+// Fragment of 32 rows x 16 k for one MFMA input: lane l gets row (l % 32), k = 8 * (l / 32) .. + 8.
+template <bool KM, int PITCH>
+__device__ __forceinline__ bf16x8_t read_fragment(const unsigned char* tile, int row0, int kk, int lane) {
+    if (!KM) {
+        const unsigned char* p = tile + (row0 + (lane & 31)) * PITCH + (kk * 16 + 8 * (lane >> 5)) * 2;
+        return *reinterpret_cast<const bf16x8_t*>(p);
+    } else {
+        // 16-lane groups: lanes 4q..4q+3 of a group address k-row q (4 x 8 bytes = 16 rows); the
+        // transposing read hands lane i of the group the 4 k-values of row i.
+        const int krow = kk * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
+        const int col = row0 + 16 * ((lane >> 4) & 1) + (lane & 3) * 4;
+        const unsigned char* p = tile + krow * PITCH + col * 2;
+        typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+        s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+        s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * PITCH));
+        typedef short s16x8_t __attribute__((ext_vector_type(8)));
+        s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8_t, v);
+    }
+}
+
+// Emits a sched_group_barrier sequence for N MFMAs: after MFMA number R come the share of `n`
+// instructions of one class (mask) whose window is MFMA slots [a, b).
+template <int R, int A, int B, int N_> struct SchedShare {
+    static constexpr int value = (R >= A && R < B) ? ((R - A + 1) * N_ / (B - A) - (R - A) * N_ / (B - A)) : 0;
+};
+template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, int VB, int NV> struct SchedSeq {
+    static __device__ __forceinline__ void apply() {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // one MFMA
+        constexpr int r = SchedShare<R, RA, RB, NR>::value;
+        constexpr int w = SchedShare<R, WA, WB, NW>::value;
+        constexpr int v = SchedShare<R, VA, VB, NV>::value;
+        if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);             // LDS reads
+        if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);             // LDS writes
+        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);             // global loads
+        if constexpr (R + 1 < N) SchedSeq<R + 1, N, RA, RB, NR, WA, WB, NW, VA, VB, NV>::apply();
+    }
+};
+
+template <int BM, int BN, bool AKM, bool BKM, bool KTAIL, class Epi>
+__global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    using TA = typename Cfg::TA;
+    using TB = typename Cfg::TB;
+    constexpr int BK = kMfmaBK;
+    constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int PITCH = Cfg::kPitch;
-    constexpr int CH = BK / 8;                 // 16-byte chunks per tile row
-    constexpr int LA = BM * CH / NTHR, LB = BN * CH / NTHR;
-    static_assert(BM * CH % NTHR == 0 && BN * CH % NTHR == 0, "staging must divide evenly");
+    constexpr int LA = TA::kChunks, LB = TB::kChunks;
+    static_assert(LA >= 1 && LB >= 1, "tile too small for 256 threads");
     extern __shared__ __align__(16) unsigned char smem[];
+    const int M = pr.M, N = pr.N;
 
     // ---- workgroup -> tile: contiguous tile ranges per XCD (workgroup w runs on XCD w % 8),
     //      tiles ordered in bands of 8 tile-rows so one XCD's L2 sees few distinct panels.
@@ -49,54 +118,91 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_bf16_mfma_kernel(GemmOp
     const int first_m = band * GROUP;
     const int gsz = min(tiles_m - first_m, GROUP);
     const int in_band = logical - band * GROUP * tiles_n;
-    const int tile_m = first_m + in_band % gsz;
-    const int tile_n = in_band / gsz;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = (first_m + in_band % gsz) * BM;
+    const int n0 = (in_band / gsz) * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
 
-    // ---- staging assignment: chunk c = tid + i * NTHR -> (row c / CH, 16-byte chunk c % CH).
-    //      Rows past the matrix edge are clamped to the last row (their results are never stored).
-    int a_off[LA], b_off[LB];      // element offsets from the tile's first row
-    int a_lds[LA], b_lds[LB];      // byte offsets inside a stage
+    // ---- staging assignment.  KC: chunk c -> (row c / 4, k chunk c % 4); rows past the edge are
+    //      clamped.  KM: chunk c -> (k row c / (ROWS/8), column chunk c % (ROWS/8)); columns past
+    //      the readable extent are clamped.  Offsets are in elements relative to (row0, k = 0).
+    int a_off[LA], a_lds[LA], a_k[LA];
+    int b_off[LB], b_lds[LB], b_k[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        int c = tid + i * NTHR, row = c / CH, ch = c % CH;
-        a_off[i] = (min(m0 + row, M - 1) - m0) * (int)op.lda + ch * 8;
-        a_lds[i] = row * PITCH + ch * 16;
+        const int c = tid + i * 256;
+        if (!AKM) {
+            const int row = c >> 2, ch = c & 3;
+            a_off[i] = min(m0 + row, M - 1) * (int)pr.A.ld + ch * 8;
+            a_lds[i] = row * TA::kPitch + ch * 16;
+            a_k[i] = ch * 8;
+        } else {
+            const int krow = c / (BM / 8), ch = c % (BM / 8);
+            a_off[i] = min(m0 + ch * 8, pr.A.ext - 8);
+            a_lds[i] = krow * TA::kPitch + ch * 16;
+            a_k[i] = krow;
+        }
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-        int c = tid + i * NTHR, row = c / CH, ch = c % CH;
-        b_off[i] = (min(n0 + row, N - 1) - n0) * (int)op.ldb + ch * 8;
-        b_lds[i] = BM * PITCH + row * PITCH + ch * 16;
+        const int c = tid + i * 256;
+        if (!BKM) {
+            const int row = c >> 2, ch = c & 3;
+            b_off[i] = min(n0 + row, N - 1) * (int)pr.B.ld + ch * 8;
+            b_lds[i] = TA::kBytes + row * TB::kPitch + ch * 16;
+            b_k[i] = ch * 8;
+        } else {
+            const int krow = c / (BN / 8), ch = c % (BN / 8);
+            b_off[i] = min(n0 + ch * 8, pr.B.ext - 8);
+            b_lds[i] = TA::kBytes + krow * TB::kPitch + ch * 16;
+            b_k[i] = krow;
+        }
     }
-    const int nk0 = op.Kc / BK;
-    const int nk = nk0 + (op.A2 ? op.Kc2 / BK : 0);
-    const bf16_t* a_base0 = op.A + (int64_t)m0 * op.lda;
-    const bf16_t* b_base0 = op.B + (int64_t)n0 * op.ldb;
-    const bf16_t* a_base1 = op.A2 ? op.A2 + (int64_t)m0 * op.lda2 : nullptr;
-    const bf16_t* b_base1 = op.B2 ? op.B2 + (int64_t)n0 * op.ldb2 : nullptr;
+    const int nk0 = (pr.Kc + BK - 1) / BK;
+    const int nk = nk0 + (pr.Kc2 + BK - 1) / BK;
+    const int lda = (int)pr.A.ld, ldb = (int)pr.B.ld;
 
-    u32x4_t ra[LA], rb[LB];
-    auto fetch = [&](int kt) {
+    u32x4_t ga[2][LA], gb[2][LB];   // two slices in flight from global memory
+    // global -> registers for k-slice kt (clamped to the last slice so the loop body has no branch)
+    auto fetch = [&](int buf, int kt) {
+        kt = min(kt, nk - 1);
         const bool seg = kt >= nk0;
-        const int koff = (seg ? kt - nk0 : kt) * BK;
-        const bf16_t* ab = (seg ? a_base1 : a_base0) + koff;
-        const bf16_t* bb = (seg ? b_base1 : b_base0) + koff;
+        const int klen = seg ? pr.Kc2 : pr.Kc;
+        const int kwant = (seg ? kt - nk0 : kt) * BK;                             // first k still to accumulate
+        const int kfrom = KTAIL ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;     // first k read
+        const bf16_t* ap = (seg ? pr.A.p2 : pr.A.p) + (AKM ? (int64_t)kfrom * lda : (int64_t)kfrom);
+        const bf16_t* bp = (seg ? pr.B.p2 : pr.B.p) + (BKM ? (int64_t)kfrom * ldb : (int64_t)kfrom);
 #pragma unroll
-        for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4_t*>(ab + a_off[i]);
+        for (int i = 0; i < LA; ++i) {
+            int off;
+            if (AKM) off = (KTAIL ? min(a_k[i], klen - 1 - kfrom) : a_k[i]) * lda + a_off[i];
+            else off = a_off[i];
+            ga[buf][i] = *reinterpret_cast<const u32x4_t*>(ap + off);
+            if (KTAIL) {
+                const int k = kfrom + a_k[i];
+                if (k < kwant || k >= klen) ga[buf][i] = u32x4_t{0, 0, 0, 0};
+            }
+        }
 #pragma unroll
-        for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4_t*>(bb + b_off[i]);
+        for (int i = 0; i < LB; ++i) {
+            int off;
+            if (BKM) off = (KTAIL ? min(b_k[i], klen - 1 - kfrom) : b_k[i]) * ldb + b_off[i];
+            else off = b_off[i];
+            gb[buf][i] = *reinterpret_cast<const u32x4_t*>(bp + off);
+            if (KTAIL) {
+                const int k = kfrom + b_k[i];
+                if (k < kwant || k >= klen) gb[buf][i] = u32x4_t{0, 0, 0, 0};
+            }
+        }
     };
-    auto stash = [&](int stage) {
+    auto stash = [&](int buf, int stage) {
         unsigned char* base = smem + stage * Cfg::kStage;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + a_lds[i]) = ra[i];
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + a_lds[i]) = ga[buf][i];
 #pragma unroll
-        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + b_lds[i]) = rb[i];
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + b_lds[i]) = gb[buf][i];
     };
 
     f32x16_t acc[TM][TN];
@@ -107,59 +213,125 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_nt_bf16_mfma_kernel(GemmOp
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // fragment addresses inside a stage: row (lane % 32), k offset 8 * (lane / 32) elements
-    const int frag_off = (lane & 31) * PITCH + (lane >> 5) * 16;
-    const int a_frag0 = (wm0)*PITCH + frag_off;                 // A rows (m) -> MFMA B input
-    const int b_frag0 = BM * PITCH + (wn0)*PITCH + frag_off;    // B rows (n) -> MFMA A input
-
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) fetch(kt + 1);
-        const unsigned char* base = smem + (kt & 1) * Cfg::kStage;
+    constexpr int NREAD = TN * (BKM ? 2 : 1) + TM * (AKM ? 2 : 1);    // LDS reads per half slice
+    bf16x8_t fm[2][TM], fn[2][TN];
+    auto load_frags = [&](int buf, int stage, int kk) {
+        const unsigned char* base = smem + stage * Cfg::kStage;
+        // order of use by mma(): fm[0] with every fn[j] first, then fm[1], ...
+        fm[buf][0] = read_fragment<AKM, TA::kPitch>(base, wm0, kk, lane);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t fn[TN], fm[TM];
+        for (int j = 0; j < TN; ++j) fn[buf][j] = read_fragment<BKM, TB::kPitch>(base + TA::kBytes, wn0 + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 1; i < TM; ++i) fm[buf][i] = read_fragment<AKM, TA::kPitch>(base, wm0 + i * 32, kk, lane);
+    };
+    auto mma = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fn[j] = *reinterpret_cast<const bf16x8_t*>(base + b_frag0 + j * 32 * PITCH + kk * 32);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fm[i] = *reinterpret_cast<const bf16x8_t*>(base + a_frag0 + i * 32 * PITCH + kk * 32);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[j], fm[i], acc[i][j], 0, 0, 0);
-        }
-        if (more) stash((kt + 1) & 1);
-        __syncthreads();
-    }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[buf][j], fm[buf][i], acc[i][j], 0, 0, 0);
+    };
 
-    // ---- epilogue: acc[i][j][4*ii + r] is C[m, n] with m = .. + lane % 32, n = .. + 8*ii + 4*(lane/32) + r
+    // ---- prologue: slices 0 and 1 into LDS, slices 2 and 3 into registers
+    fetch(0, 0);
+    fetch(1, 1);
+    stash(0, 0);
+    stash(1, 1);
+    fetch(0, 2);
+    fetch(1, 3);
+    __syncthreads();
+    load_frags(0, 0, 0);
+
+    int st_cur = 0, st_next = 1, st_fill = 2;
+    // One k-slice.  On entry fragment buffer 0 holds the first half of slice kt; register set
+    // `buf` holds slice kt+2.  LDS reads are issued ahead of the LDS writes in program order (the
+    // compiler cannot tell the stages apart) and everything is spread between the MFMAs.
+    auto slice = [&](auto buf_c, int kt) {
+        constexpr int buf = decltype(buf_c)::value;
+        load_frags(1, st_cur, 1);       // second half of slice kt
+        stash(buf, st_fill);            // slice kt+2 -> LDS (its stage was last read in slice kt-1)
+        mma(0);
+        fetch(buf, kt + 4);             // slice kt+4 -> registers
+        load_frags(0, st_next, 0);      // first half of slice kt+1 (visible since the last barrier)
+        mma(1);
+        // first half: the fragment reads go out with the first quarter of the MFMAs, the LDS writes
+        // with the rest; second half: fragment reads with the first half of the MFMAs, global loads
+        // spread over all of them (measured best of several spreads).
+        constexpr int NM = TM * TN;
+        SchedSeq<0, NM, 0, NM / 4, NREAD, NM / 4, NM, LA + LB, 0, 0, 0>::apply();
+        SchedSeq<0, NM, 0, NM / 2, NREAD, 0, 0, 0, 0, NM, LA + LB>::apply();
+        __syncthreads();
+        const int t = st_cur;
+        st_cur = st_next;
+        st_next = st_fill;
+        st_fill = t;
+    };
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        slice(std::integral_constant<int, 0>{}, kt);
+        slice(std::integral_constant<int, 1>{}, kt + 1);
+    }
+    if (kt < nk) slice(std::integral_constant<int, 0>{}, kt);
+
+    // ---- epilogue.  acc[i][j][4*ii + r] is C[m, n] with m = .. + lane % 32 and n = .. + 8*ii +
+    //      4*(lane/32) + r: a lane owns 4 consecutive n of 32 different rows, which would make
+    //      scattered 8/16-byte global stores.  Each wave therefore turns its 32-row blocks around
+    //      in a private LDS area (the stages are free after the last barrier) and hands the
+    //      epilogue functor whole row segments: 32 lanes x 4 columns = 128 consecutive columns.
+    {
+        constexpr int EPITCH = WN * 4 + 16;                       // bytes per staged row (fp32)
+        static_assert(4 * 32 * EPITCH <= Cfg::kLds, "epilogue staging must fit in the stage memory");
+        unsigned char* area = smem + wave * (32 * EPITCH);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm0 + i * 32 + (lane & 31);
-        if (m >= M) continue;
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                const int n = n0 + wn0 + j * 32 + 8 * ii + 4 * (lane >> 5);
-                float v[4] = {acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
-                epi.store4(m, n, v);
+                for (int ii = 0; ii < 4; ++ii) {
+                    const int col = j * 32 + 8 * ii + 4 * (lane >> 5);
+                    *reinterpret_cast<f32x4_t*>(area + (lane & 31) * EPITCH + col * 4) =
+                        f32x4_t{acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int LPR = WN / 4;                            // lanes per staged row
+            constexpr int RPI = 64 / LPR;                          // rows per instruction
+#pragma unroll 1
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int row = it * RPI + lane / LPR, c4 = lane % LPR;
+                const f32x4_t t = *reinterpret_cast<const f32x4_t*>(area + row * EPITCH + c4 * 16);
+                const int m = m0 + wm0 + i * 32 + row;
+                const float v[4] = {t[0], t[1], t[2], t[3]};
+                if (m < M) epi.store4(m, n0 + wn0 + c4 * 4, v);
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
-inline hipError_t launch_gemm_nt_bf16_mfma_cfg(const GemmOperands<bf16_t>& op, int M, int N, const Epi& epi,
-                                               hipStream_t st) {
-    using Cfg = MfmaCfg<BM, BN, BK, WGM, WGN>;
-    auto kern = gemm_nt_bf16_mfma_kernel<BM, BN, BK, WGM, WGN, Epi>;
+// Host-side check of the kernel's layout assumptions (the caller vouches for the zero padding of
+// k-contiguous operands past a contraction length that is not a multiple of 8).
+inline bool mfma_problem_ok(const MfmaProblem& p) {
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    auto operand_ok = [&](const GemmOperand<bf16_t>& o, int rows, bool two) {
+        bool ok = o.p && al16(o.p) && o.ld % 8 == 0 && (!two || (o.p2 && al16(o.p2)));
+        if (o.km) ok = ok && o.ext % 8 == 0 && o.ext >= 8 && o.ext <= o.ld && rows <= o.ext;
+        // element offsets inside a tile are kept in 32 bits
+        ok = ok && (int64_t)(o.km ? kMfmaBK : rows) * o.ld < (1ll << 31);
+        return ok;
+    };
+    const bool two = p.Kc2 != 0;
+    bool ok = p.M >= 1 && p.N >= 1 && p.Kc >= kMfmaBK && (!two || p.Kc2 >= kMfmaBK);
+    return ok && operand_ok(p.A, p.M, two) && operand_ok(p.B, p.N, two);
+}
+
+template <int BM, int BN, bool AKM, bool BKM, bool KTAIL, class Epi>
+inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, KTAIL, Epi>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -167,18 +339,9 @@ inline hipError_t launch_gemm_nt_bf16_mfma_cfg(const GemmOperands<bf16_t>& op, i
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(Cfg::kThreads), Cfg::kLds, st, op, M, N, tiles_m,
-                       tiles_n, epi);
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
     return hipGetLastError();
-}
-
-// True when the MFMA kernel's layout assumptions hold for this operand set.
-inline bool mfma_operands_ok(const GemmOperands<bf16_t>& op) {
-    auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    bool ok = op.Kc > 0 && op.Kc % 64 == 0 && op.lda % 8 == 0 && op.ldb % 8 == 0 && al16(op.A) && al16(op.B);
-    if (op.A2) ok = ok && op.Kc2 > 0 && op.Kc2 % 64 == 0 && op.lda2 % 8 == 0 && op.ldb2 % 8 == 0 && al16(op.A2) && al16(op.B2);
-    return ok;
 }
 
 }  // namespace moc

@@ -1,42 +1,9 @@
-// Small bandwidth-bound kernels around the GEMMs: transposes, the selection bit mask for the
-// backward, padding clears, RMSNorm and the residual add.
+// Small bandwidth-bound kernels around the GEMMs: the selection bit mask for the backward,
+// RMSNorm and the residual add.
 #pragma once
 #include "common.h"
 
 namespace moc {
-
-// out[c, r] = in[r, c] for r < R, c < C; columns r in [R, ld_out) of out are set to zero so the
-// result can be contracted over its padded leading dimension.
-template <class E>
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const E* __restrict__ in, int64_t ld_in, int R, int C,
-                                                            E* __restrict__ out, int64_t ld_out) {
-    __shared__ E tile[64][65];
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        int r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < R && c < C) ? in[(int64_t)r * ld_in + c] : E(0);
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        int c = c0 + i, r = r0 + tx;
-        if (c < C && r < ld_out) out[(int64_t)c * ld_out + r] = tile[tx][i];
-    }
-}
-
-// Zero columns [c_begin, ld) of up to three [rows, ld] arrays.
-template <class E>
-__global__ void zero_cols_kernel(E* a0, E* a1, E* a2, int rows, int c_begin, int64_t ld) {
-    const int width = (int)ld - c_begin;
-    const int64_t n = (int64_t)rows * width;
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        int64_t r = i / width;
-        int c = c_begin + (int)(i % width);
-        a0[r * ld + c] = E(0);
-        if (a1) a1[r * ld + c] = E(0);
-        if (a2) a2[r * ld + c] = E(0);
-    }
-}
 
 // From idx[T, K] (ascending per row) build the selection bit mask maskw[T, nw] (bit j % 32 of word
 // j / 32) and pref[T, nw], the number of selected channels before each word.  One workgroup per

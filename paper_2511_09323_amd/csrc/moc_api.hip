@@ -143,39 +143,33 @@ moc_status check_shape(const moc_shape* s, bool decode) {
     } while (0)
 
 // ------------------------------------------------------------------------ GEMM dispatch
-template <class E, class Epi>
-moc_status run_gemm(const char* name, const GemmOperands<E>& op, int M, int N, const Epi& epi, hipStream_t st) {
+template <int BM, int BN, bool AKM, bool BKM, class Epi>
+hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t st) {
+    const bool tail = pr.Kc % kMfmaBK != 0 || pr.Kc2 % kMfmaBK != 0;
+    return tail ? launch_gemm_bf16_mfma<BM, BN, AKM, BKM, true, Epi>(pr, epi, st)
+                : launch_gemm_bf16_mfma<BM, BN, AKM, BKM, false, Epi>(pr, epi, st);
+}
+
+// Runs C = A B^T (+ second segment) with the epilogue `epi`.  AKM / BKM state the operand layouts
+// at compile time (they must match pr.A.km / pr.B.km).  bf16 problems that satisfy the MFMA
+// kernel's assumptions go to the matrix cores, everything else to the generic kernel.
+template <class E, bool AKM, bool BKM, class Epi>
+moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, hipStream_t st) {
     Span span(name, st);
     if constexpr (std::is_same<E, bf16_t>::value) {
-        if (!options().force_generic && mfma_operands_ok(op)) {
+        if (!options().force_generic && mfma_problem_ok(pr)) {
             int tile = options().tile;
             if (tile == 0) {
-                const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-                tile = t256 >= 192 ? 256 : 128;
+                const int64_t t256 = (int64_t)((pr.M + 255) / 256) * ((pr.N + 255) / 256);
+                tile = t256 >= 128 ? 256 : 128;
             }
-            hipError_t e = tile == 256 ? launch_gemm_nt_bf16_mfma_cfg<256, 256, 64, 2, 2>(op, M, N, epi, st)
-                                       : launch_gemm_nt_bf16_mfma_cfg<128, 128, 64, 2, 2>(op, M, N, epi, st);
+            hipError_t e = tile == 256 ? launch_mfma_tail<256, 256, AKM, BKM, Epi>(pr, epi, st)
+                                       : launch_mfma_tail<128, 128, AKM, BKM, Epi>(pr, epi, st);
             if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
             return MOC_OK;
         }
     }
-    launch_gemm_nt_generic<E, Epi>(op, M, N, epi, st);
-    HIP_TRY(hipGetLastError());
-    return MOC_OK;
-}
-
-template <class E>
-GemmOperands<E> operands(const E* A, int64_t lda, const E* B, int64_t ldb, int Kc, const E* A2 = nullptr,
-                         const E* B2 = nullptr, int Kc2 = 0) {
-    return GemmOperands<E>{A, B, lda, ldb, Kc, A2, B2, lda, ldb, Kc2};
-}
-
-template <class E>
-moc_status run_transpose(const char* name, const E* in, int64_t ld_in, int R, int C, E* out, int64_t ld_out,
-                         hipStream_t st) {
-    Span span(name, st);
-    dim3 grid((unsigned)((ld_out + 63) / 64), (unsigned)((C + 63) / 64));
-    hipLaunchKernelGGL((transpose_pad_kernel<E>), grid, dim3(256), 0, st, in, ld_in, R, C, out, ld_out);
+    launch_gemm_generic<E, Epi>(pr, epi, st);
     HIP_TRY(hipGetLastError());
     return MOC_OK;
 }
@@ -200,46 +194,38 @@ moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t s
 // ------------------------------------------------------------------- workspace layouts
 struct Dims {
     int T, d, F, K;
-    int ldF, ldT, nw;
+    int ldF, nw;
     explicit Dims(const moc_shape& s) : T(s.T), d(s.d), F(s.F), K(s.K) {
         ldF = round_up(F, 64);
-        ldT = round_up(T, 64);
         nw = ldF / 32;
     }
 };
 
-template <class E> struct FwdWs {
+template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gate, U, masked Z'
     float* G;
-    E *U, *Zd, *WdT;
+    E *U, *Zd;
     size_t bytes;
     FwdWs(void* ws, const Dims& D, bool dense) {
         Carver c(ws);
         G = dense ? nullptr : c.take<float>((size_t)D.T * D.ldF);
         U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
         Zd = c.take<E>((size_t)D.T * D.ldF);
-        WdT = c.take<E>((size_t)D.d * D.ldF);
         bytes = c.off;
     }
 };
 
-template <class E> struct BwdWs {
+template <class E> struct BwdWs {      // selection bit mask and the three dense [T, ldF] operands
     uint32_t* maskw;
     uint16_t* pref;
-    E *dGd, *dUd, *ZT, *dGT, *dUT, *XT, *dYT, *WgT, *WuT;
+    E *Zd, *dGd, *dUd;
     size_t bytes;
     BwdWs(void* ws, const Dims& D, bool dense) {
         Carver c(ws);
         maskw = dense ? nullptr : c.take<uint32_t>((size_t)D.T * D.nw);
         pref = dense ? nullptr : c.take<uint16_t>((size_t)D.T * D.nw);
+        Zd = c.take<E>((size_t)D.T * D.ldF);
         dGd = c.take<E>((size_t)D.T * D.ldF);
         dUd = c.take<E>((size_t)D.T * D.ldF);
-        ZT = c.take<E>((size_t)D.F * D.ldT);
-        dGT = c.take<E>((size_t)D.F * D.ldT);
-        dUT = c.take<E>((size_t)D.F * D.ldT);
-        XT = c.take<E>((size_t)D.d * D.ldT);
-        dYT = c.take<E>((size_t)D.d * D.ldT);
-        WgT = c.take<E>((size_t)D.d * D.ldF);
-        WuT = c.take<E>((size_t)D.d * D.ldF);
         bytes = c.off;
     }
 };
@@ -275,25 +261,29 @@ template <class E> size_t workspace_for(const Dims& D, int op) {
     return 0;
 }
 
+// D = Z' W_down (Eq. MoC-2 / FFN-2): Z' is [T, ldF] with zeros past F, W_down [F, d] is read k-major.
+template <class E>
+moc_status down_projection(const Dims& D, const E* Zd, const E* wd, E* y, hipStream_t st) {
+    GemmProblem<E> pr{kc_operand<E>(Zd, D.ldF), km_operand<E>(wd, D.d, D.d), D.T, D.d, D.F, 0};
+    return run_gemm<E, false, true>("gemm_down", pr, EpiStore<E>{y, D.d, D.d, 0}, st);
+}
+
 // ----------------------------------------------------------------------------- forward
 template <class E>
 moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx, E* gvals,
                     E* uvals, void* ws, hipStream_t st) {
     FwdWs<E> W(ws, D, false);
     moc_status s;
-    if ((s = run_transpose<E>("transpose_wd", wd, D.d, D.F, D.d, W.WdT, D.ldF, st)) != MOC_OK) return s;
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
-    if ((s = run_gemm<E>("gemm_gate", operands<E>(x, D.d, wg, D.d, D.d), D.T, D.F,
-                         EpiStore<float>{W.G, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
+    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0};
+    if ((s = run_gemm<E, false, false>("gemm_gate", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // U = X W_up (Eq. MoC-1)
-    if ((s = run_gemm<E>("gemm_up", operands<E>(x, D.d, wu, D.d, D.d), D.T, D.F, EpiStore<E>{W.U, D.ldF, D.F, 0},
-                         st)) != MOC_OK) return s;
+    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0};
+    if ((s = run_gemm<E, false, false>("gemm_up", pu, EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
     if ((s = run_topk<E, 256, 4, true>("topk_select_act", a, D.T, st)) != MOC_OK) return s;
-    // D = Z' W_down (Eq. MoC-2)
-    return run_gemm<E>("gemm_down", operands<E>(W.Zd, D.ldF, W.WdT, D.ldF, D.ldF), D.T, D.d,
-                       EpiStore<E>{y, D.d, D.d, 0}, st);
+    return down_projection<E>(D, W.Zd, wd, y, st);
 }
 
 // ---------------------------------------------------------------------------- backward
@@ -309,31 +299,21 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                            W.maskw, W.pref);
         HIP_TRY(hipGetLastError());
     }
-    if ((s = run_transpose<E>("transpose_x", x, D.d, D.T, D.d, W.XT, D.ldT, st)) != MOC_OK) return s;
-    if ((s = run_transpose<E>("transpose_dy", dy, D.d, D.T, D.d, W.dYT, D.ldT, st)) != MOC_OK) return s;
-    if ((s = run_transpose<E>("transpose_wg", wg, D.d, D.F, D.d, W.WgT, D.ldF, st)) != MOC_OK) return s;
-    if ((s = run_transpose<E>("transpose_wu", wu, D.d, D.F, D.d, W.WuT, D.ldF, st)) != MOC_OK) return s;
-    if (D.ldT > D.T) {
-        Span span("zero_pad", st);
-        hipLaunchKernelGGL((zero_cols_kernel<E>), dim3(256), dim3(256), 0, st, W.ZT, W.dGT, W.dUT, D.F, D.T,
-                           (int64_t)D.ldT);
-        HIP_TRY(hipGetLastError());
-    }
     // dZ' = dD W_down^T (bp-1) with the pointwise part (bp-2, bp-3) in the epilogue
-    EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.dGd, W.dUd,
-                                  W.ZT,    W.dGT,  W.dUT, D.F,  D.ldF, D.ldT};
-    if ((s = run_gemm<E>("gemm_dz_pointwise", operands<E>(dy, D.d, wd, D.d, D.d), D.T, D.F, epi, st)) != MOC_OK)
-        return s;
-    // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens
-    if ((s = run_gemm<E>("gemm_dwd", operands<E>(W.ZT, D.ldT, W.dYT, D.ldT, D.ldT), D.F, D.d,
-                         EpiStore<E>{dwd, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    if ((s = run_gemm<E>("gemm_dwg", operands<E>(W.dGT, D.ldT, W.XT, D.ldT, D.ldT), D.F, D.d,
-                         EpiStore<E>{dwg, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    if ((s = run_gemm<E>("gemm_dwu", operands<E>(W.dUT, D.ldT, W.XT, D.ldT, D.ldT), D.F, D.d,
-                         EpiStore<E>{dwu, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.Zd, W.dGd, W.dUd, D.F, D.ldF};
+    GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0};
+    if ((s = run_gemm<E, false, false>("gemm_dz_pointwise", pz, epi, st)) != MOC_OK) return s;
+    // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens,
+    // both operands read k-major (token index leading)
+    GemmProblem<E> pwd{km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0};
+    if ((s = run_gemm<E, true, true>("gemm_dwd", pwd, EpiStore<E>{dwd, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    GemmProblem<E> pwg{km_operand<E>(W.dGd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0};
+    if ((s = run_gemm<E, true, true>("gemm_dwg", pwg, EpiStore<E>{dwg, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    GemmProblem<E> pwu{km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0};
+    if ((s = run_gemm<E, true, true>("gemm_dwu", pwu, EpiStore<E>{dwu, D.d, D.d, 0}, st)) != MOC_OK) return s;
     // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
-    return run_gemm<E>("gemm_dx", operands<E>(W.dGd, D.ldF, W.WgT, D.ldF, D.ldF, W.dUd, W.WuT, D.ldF), D.T, D.d,
-                       EpiStore<E>{dx, D.d, D.d, 0}, st);
+    GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F};
+    return run_gemm<E, false, true>("gemm_dx", px, EpiStore<E>{dx, D.d, D.d, 0}, st);
 }
 
 // ------------------------------------------------------------------------ dense SwiGLU
@@ -342,13 +322,12 @@ moc_status swiglu_fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, 
                            E* u_save, void* ws, hipStream_t st) {
     FwdWs<E> W(ws, D, true);
     moc_status s;
-    if ((s = run_transpose<E>("transpose_wd", wd, D.d, D.F, D.d, W.WdT, D.ldF, st)) != MOC_OK) return s;
-    if ((s = run_gemm<E>("gemm_gate_dense", operands<E>(x, D.d, wg, D.d, D.d), D.T, D.F,
-                         EpiStore<E>{g_save, D.F, D.F, 0}, st)) != MOC_OK) return s;
-    if ((s = run_gemm<E>("gemm_up_act_dense", operands<E>(x, D.d, wu, D.d, D.d), D.T, D.F,
-                         EpiSwigluAct<E>{g_save, u_save, W.Zd, D.F, D.ldF}, st)) != MOC_OK) return s;
-    return run_gemm<E>("gemm_down", operands<E>(W.Zd, D.ldF, W.WdT, D.ldF, D.ldF), D.T, D.d,
-                       EpiStore<E>{y, D.d, D.d, 0}, st);
+    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0};
+    if ((s = run_gemm<E, false, false>("gemm_gate_dense", pg, EpiStore<E>{g_save, D.F, D.F, 0}, st)) != MOC_OK) return s;
+    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0};
+    if ((s = run_gemm<E, false, false>("gemm_up_act_dense", pu, EpiSwigluAct<E>{g_save, u_save, W.Zd, D.F, D.ldF}, st)) != MOC_OK)
+        return s;
+    return down_projection<E>(D, W.Zd, wd, y, st);
 }
 
 // ------------------------------------------------------------------------------ decode
