@@ -24,6 +24,7 @@ template <class E> struct GemmProblem {
     GemmOperand<E> A, B;
     int M, N;
     int Kc, Kc2;    // contraction lengths of segment 0 and 1 (Kc2 = 0: single segment)
+    bool kc_zero_padded;   // the k-contiguous operand holds zeros from Kc up to the next multiple of 32
 };
 
 template <class E> inline GemmOperand<E> kc_operand(const E* p, int64_t ld, const E* p2 = nullptr) {

@@ -21,12 +21,14 @@
 // a lane ends up with four consecutive n for one m -- the shape the epilogues want.
 //
 // Requirements checked by the host: 16-byte aligned bases, leading dimensions multiples of 8,
-// contraction lengths >= 32; a KC operand must be readable up to the next multiple of 8 past the
-// contraction length and hold zeros there (or meet zeros of the other operand); a KM operand must
-// be readable up to `ext` columns (multiple of 8).  Contraction tails (length % 32 != 0) use the
-// KTAIL instantiation: the last slice re-reads the final 32-wide window (8-aligned) and zeroes
-// what lies before the part still to be accumulated or past the end; k-major rows past the end
-// are clamped to the last row before being zeroed.
+// contraction lengths >= 32; a KM operand must be readable up to `ext` columns (multiple of 8).
+// Contraction lengths that are not multiples of 32 take one of two tail modes:
+//   TAILMODE 2 ("padded"): one operand is KC, readable and zero up to the next multiple of 32
+//     (the library's own dense intermediates are), the other is KM: the KM k-rows past the end
+//     are clamped to the last row and meet those zeros.  Nearly free.
+//   TAILMODE 1 (general): the last slice re-reads the final 32-wide window (8-aligned, so a KC
+//     operand must be readable and zero up to the next multiple of 8) and zeroes what lies
+//     before the part still to be accumulated or past the end; KM rows are clamped as well.
 #pragma once
 #include <type_traits>
 
@@ -94,7 +96,7 @@ template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, 
     }
 };
 
-template <int BM, int BN, bool AKM, bool BKM, bool KTAIL, class Epi>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
@@ -170,28 +172,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
         kt = min(kt, nk - 1);
         const bool seg = kt >= nk0;
         const int klen = seg ? pr.Kc2 : pr.Kc;
-        const int kwant = (seg ? kt - nk0 : kt) * BK;                             // first k still to accumulate
-        const int kfrom = KTAIL ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;     // first k read
+        const int kwant = (seg ? kt - nk0 : kt) * BK;                                   // first k still to accumulate
+        const int kfrom = TAILMODE == 1 ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;   // first k read
+        const int klast = klen - 1 - kfrom;                                              // last valid k row of this slice
         const bf16_t* ap = (seg ? pr.A.p2 : pr.A.p) + (AKM ? (int64_t)kfrom * lda : (int64_t)kfrom);
         const bf16_t* bp = (seg ? pr.B.p2 : pr.B.p) + (BKM ? (int64_t)kfrom * ldb : (int64_t)kfrom);
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
-            int off;
-            if (AKM) off = (KTAIL ? min(a_k[i], klen - 1 - kfrom) : a_k[i]) * lda + a_off[i];
-            else off = a_off[i];
+            int off = a_off[i];
+            if (AKM) off += (TAILMODE ? min(a_k[i] * lda, klast * lda) : a_k[i] * lda);
             ga[buf][i] = *reinterpret_cast<const u32x4_t*>(ap + off);
-            if (KTAIL) {
+            if (TAILMODE == 1) {
                 const int k = kfrom + a_k[i];
                 if (k < kwant || k >= klen) ga[buf][i] = u32x4_t{0, 0, 0, 0};
             }
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
-            int off;
-            if (BKM) off = (KTAIL ? min(b_k[i], klen - 1 - kfrom) : b_k[i]) * ldb + b_off[i];
-            else off = b_off[i];
+            int off = b_off[i];
+            if (BKM) off += (TAILMODE ? min(b_k[i] * ldb, klast * ldb) : b_k[i] * ldb);
             gb[buf][i] = *reinterpret_cast<const u32x4_t*>(bp + off);
-            if (KTAIL) {
+            if (TAILMODE == 1) {
                 const int k = kfrom + b_k[i];
                 if (k < kwant || k >= klen) gb[buf][i] = u32x4_t{0, 0, 0, 0};
             }
@@ -328,10 +329,10 @@ inline bool mfma_problem_ok(const MfmaProblem& p) {
     return ok && operand_ok(p.A, p.M, two) && operand_ok(p.B, p.N, two);
 }
 
-template <int BM, int BN, bool AKM, bool BKM, bool KTAIL, class Epi>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi>
 inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
-    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, KTAIL, Epi>;
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

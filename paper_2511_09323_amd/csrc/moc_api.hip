@@ -146,8 +146,14 @@ moc_status check_shape(const moc_shape* s, bool decode) {
 template <int BM, int BN, bool AKM, bool BKM, class Epi>
 hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t st) {
     const bool tail = pr.Kc % kMfmaBK != 0 || pr.Kc2 % kMfmaBK != 0;
-    return tail ? launch_gemm_bf16_mfma<BM, BN, AKM, BKM, true, Epi>(pr, epi, st)
-                : launch_gemm_bf16_mfma<BM, BN, AKM, BKM, false, Epi>(pr, epi, st);
+    if (!tail) return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi>(pr, epi, st);
+    if constexpr (AKM != BKM) {
+        const GemmOperand<bf16_t>& kc = AKM ? pr.B : pr.A;
+        const int kmax = std::max(pr.Kc, pr.Kc2);
+        if (pr.kc_zero_padded && kc.ld >= round_up(kmax, kMfmaBK))
+            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 2, Epi>(pr, epi, st);
+    }
+    return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 1, Epi>(pr, epi, st);
 }
 
 // Runs C = A B^T (+ second segment) with the epilogue `epi`.  AKM / BKM state the operand layouts
@@ -174,11 +180,12 @@ moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, 
     return MOC_OK;
 }
 
+// LDS-resident Top-K: any row length up to the LDS capacity, any alignment.
 template <class E, int NT, int VEC, bool FUSED>
-moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
+moc_status run_topk_lds(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
     const size_t lds = topk_lds_bytes(a.F, NT, VEC);
     if (lds > 160 * 1024 - 64) return fail(MOC_ERR_UNSUPPORTED, "F = %d needs %zu bytes of LDS for Top-K", a.F, lds);
-    auto kern = topk_rows_kernel<E, NT, VEC, FUSED>;
+    auto kern = topk_rows_lds_kernel<E, NT, VEC, FUSED>;
     static size_t attr_bytes = 0;
     if (lds > attr_bytes) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -189,6 +196,37 @@ moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t s
     hipLaunchKernelGGL(kern, dim3(T), dim3(NT), lds, st, a);
     HIP_TRY(hipGetLastError());
     return MOC_OK;
+}
+
+template <class E, int NT, int NCH, bool FUSED>
+moc_status launch_topk_reg(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
+    Span span(name, st);
+    hipLaunchKernelGGL((topk_rows_kernel<E, NT, NCH, FUSED>), dim3(T), dim3(NT), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+// Row Top-K with NT threads per row.  Rows that are 16-byte aligned and short enough stay in
+// registers; everything else goes through the LDS-resident kernel.
+template <class E, int NT, bool FUSED>
+moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
+    const bool aligned = a.ldg % 4 == 0 && aligned16(a.g);
+    const int cover = FUSED ? (int)std::max<int64_t>(a.F, a.ldz) : a.F;
+    const int nch = (cover + NT * 4 - 1) / (NT * 4);
+    if (aligned) {
+        if (nch <= 1) return launch_topk_reg<E, NT, 1, FUSED>(name, a, T, st);
+        if (nch <= 2) return launch_topk_reg<E, NT, 2, FUSED>(name, a, T, st);
+        if (nch <= 3) return launch_topk_reg<E, NT, 3, FUSED>(name, a, T, st);
+        if (NT == 256) {
+            if (nch <= 4) return launch_topk_reg<E, NT, 4, FUSED>(name, a, T, st);
+            if (nch <= 6) return launch_topk_reg<E, NT, 6, FUSED>(name, a, T, st);
+            if (nch <= 8) return launch_topk_reg<E, NT, 8, FUSED>(name, a, T, st);
+            if (nch <= 11) return launch_topk_reg<E, NT, 11, FUSED>(name, a, T, st);
+        }
+        return run_topk_lds<E, NT, 4, FUSED>(name, a, T, st);
+    }
+    if (FUSED) return fail(MOC_ERR_BAD_ARG, "%s: unaligned workspace", name);
+    return run_topk_lds<E, NT, 1, FUSED>(name, a, T, st);
 }
 
 // ------------------------------------------------------------------- workspace layouts
@@ -264,7 +302,7 @@ template <class E> size_t workspace_for(const Dims& D, int op) {
 // D = Z' W_down (Eq. MoC-2 / FFN-2): Z' is [T, ldF] with zeros past F, W_down [F, d] is read k-major.
 template <class E>
 moc_status down_projection(const Dims& D, const E* Zd, const E* wd, E* y, hipStream_t st) {
-    GemmProblem<E> pr{kc_operand<E>(Zd, D.ldF), km_operand<E>(wd, D.d, D.d), D.T, D.d, D.F, 0};
+    GemmProblem<E> pr{kc_operand<E>(Zd, D.ldF), km_operand<E>(wd, D.d, D.d), D.T, D.d, D.F, 0, true};
     return run_gemm<E, false, true>("gemm_down", pr, EpiStore<E>{y, D.d, D.d, 0}, st);
 }
 
@@ -275,14 +313,14 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     FwdWs<E> W(ws, D, false);
     moc_status s;
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
-    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0};
+    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm<E, false, false>("gemm_gate", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // U = X W_up (Eq. MoC-1)
-    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0};
+    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm<E, false, false>("gemm_up", pu, EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
-    if ((s = run_topk<E, 256, 4, true>("topk_select_act", a, D.T, st)) != MOC_OK) return s;
+    if ((s = run_topk<E, 256, true>("topk_select_act", a, D.T, st)) != MOC_OK) return s;
     return down_projection<E>(D, W.Zd, wd, y, st);
 }
 
@@ -301,18 +339,18 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     }
     // dZ' = dD W_down^T (bp-1) with the pointwise part (bp-2, bp-3) in the epilogue
     EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.Zd, W.dGd, W.dUd, D.F, D.ldF};
-    GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0};
+    GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm<E, false, false>("gemm_dz_pointwise", pz, epi, st)) != MOC_OK) return s;
     // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens,
     // both operands read k-major (token index leading)
-    GemmProblem<E> pwd{km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0};
+    GemmProblem<E> pwd{km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0, false};
     if ((s = run_gemm<E, true, true>("gemm_dwd", pwd, EpiStore<E>{dwd, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    GemmProblem<E> pwg{km_operand<E>(W.dGd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0};
+    GemmProblem<E> pwg{km_operand<E>(W.dGd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false};
     if ((s = run_gemm<E, true, true>("gemm_dwg", pwg, EpiStore<E>{dwg, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    GemmProblem<E> pwu{km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0};
+    GemmProblem<E> pwu{km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false};
     if ((s = run_gemm<E, true, true>("gemm_dwu", pwu, EpiStore<E>{dwu, D.d, D.d, 0}, st)) != MOC_OK) return s;
     // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
-    GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F};
+    GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F, true};
     return run_gemm<E, false, true>("gemm_dx", px, EpiStore<E>{dx, D.d, D.d, 0}, st);
 }
 
@@ -322,9 +360,9 @@ moc_status swiglu_fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, 
                            E* u_save, void* ws, hipStream_t st) {
     FwdWs<E> W(ws, D, true);
     moc_status s;
-    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0};
+    GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm<E, false, false>("gemm_gate_dense", pg, EpiStore<E>{g_save, D.F, D.F, 0}, st)) != MOC_OK) return s;
-    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0};
+    GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm<E, false, false>("gemm_up_act_dense", pu, EpiSwigluAct<E>{g_save, u_save, W.Zd, D.F, D.ldF}, st)) != MOC_OK)
         return s;
     return down_projection<E>(D, W.Zd, wd, y, st);
@@ -362,7 +400,7 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     else s = decode_gate<E, 16>(D, x, wg, W.g, st);
     if (s != MOC_OK) return s;
     TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
-    if ((s = run_topk<float, 1024, 4, false>("decode_topk", a, B, st)) != MOC_OK) return s;
+    if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
     {
         const size_t lds = (size_t)D.d * sizeof(E);
         if (lds > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
@@ -508,8 +546,7 @@ moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_
     CHECK_PTR(g); CHECK_PTR(idx); CHECK_PTR(gsel);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     TopkArgs<float> a{g, ldg, F, K, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
-    if (ldg % 4 == 0) return run_topk<float, 256, 4, false>("topk_rows", a, T, st);
-    return run_topk<float, 256, 1, false>("topk_rows", a, T, st);
+    return run_topk<float, 256, false>("topk_rows", a, T, st);
 }
 
 moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain, float eps, void* out,

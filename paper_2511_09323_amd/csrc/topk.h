@@ -2,10 +2,14 @@
 // "Mixture-of-Channels architecture"): exactly K channels per row, the largest signed values,
 // equal values ordered by channel index (lower first), -0.0 equal to +0.0.
 //
-// One workgroup per row.  The row's order-preserving 32-bit keys are parked in LDS while a
-// most-significant-digit-first radix select (11 + 11 + 10 bits, LDS histograms) finds the key of
-// the K-th largest element; a final ordered pass ranks the selected channels with wavefront
-// ballots so that the output is ascending by channel without any sort.
+// One workgroup per row.  A most-significant-digit-first radix select on order-preserving 32-bit
+// keys finds the key of the K-th largest element: the sign bit is settled with ballots, then
+// digits of 10, 11 and 10 bits with LDS histograms.  A final ordered pass ranks the selected
+// channels with wavefront ballots, so the output ascends by channel without any sort.
+//
+// topk_rows_kernel keeps the whole row in registers (all global loads are issued before anything
+// waits on them); topk_rows_lds_kernel parks the keys in LDS instead and serves rows that are too
+// long for registers or not 16-byte aligned.
 //
 // FUSED = true is the training forward: besides idx and the gate values it gathers U at the
 // selected channels and writes the dense activation row Z' = SiLU(G) . M . U (Eq. MoC-2), zeros
@@ -16,6 +20,14 @@
 namespace moc {
 
 constexpr int kTopkBins = 2048;
+
+template <class E> __device__ __forceinline__ void store_vec4_any(E* p, const float v[4]);
+template <> __device__ __forceinline__ void store_vec4_any<float>(float* p, const float v[4]) {
+    *reinterpret_cast<f32x4_t*>(p) = f32x4_t{v[0], v[1], v[2], v[3]};
+}
+template <> __device__ __forceinline__ void store_vec4_any<bf16_t>(bf16_t* p, const float v[4]) {
+    *reinterpret_cast<u32x2_t*>(p) = u32x2_t{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+}
 
 template <class E> struct TopkArgs {
     const float* g;     // [T, ldg] fp32 gate
@@ -57,7 +69,7 @@ template <int NT> __device__ __forceinline__ int block_exclusive_scan(int v, int
 }
 
 template <class E, int NT, int VEC, bool FUSED>
-__global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
+__global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
     constexpr int NW = NT / 64;
     constexpr int CHUNK = NT * VEC;
     extern __shared__ __align__(16) unsigned char topk_smem[];
@@ -251,6 +263,211 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             for (int e = 0; e < VEC; ++e)
                 if (j0 + e < ldz_pad) Elem<E>::store(zrow + j0 + e, z[e]);
         }
+    }
+}
+
+// ---------------------------------------------------------------- register-resident variant
+// Row of up to NCH * NT * 4 channels; thread t holds channels c*NT*4 + t*4 .. +3 of every chunk c.
+template <class E, int NT, int NCH, bool FUSED>
+__global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
+    constexpr int NW = NT / 64;
+    constexpr int CHUNK = NT * 4;
+    __shared__ uint32_t hist[kTopkBins];
+    __shared__ int cnt_gt[NCH * NW], cnt_eq[NCH * NW];
+    __shared__ int red[NW];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_need;
+    const int F = a.F, K = a.K;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const float* grow = a.g + row * a.ldg;
+
+    // ---- all loads of the row up front
+    f32x4_t gv[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int j0 = c * CHUNK + tid * 4;
+        if (j0 + 3 < F) gv[c] = *reinterpret_cast<const f32x4_t*>(grow + j0);
+        else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gv[c][e] = (j0 + e < F) ? grow[j0 + e] : 0.0f;
+        }
+    }
+    u32x2_t uraw[NCH];     // FUSED, E = bf16: four packed values; E = float handled below
+    f32x4_t uf[NCH];
+    if (FUSED) {
+        const E* urow = a.u + row * a.ldu;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int j0 = c * CHUNK + tid * 4;
+            if (sizeof(E) == 2) {
+                uraw[c] = u32x2_t{0, 0};
+                if (j0 < a.ldu) uraw[c] = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const bf16_t*>(urow) + j0);
+            } else {
+                uf[c] = f32x4_t{0, 0, 0, 0};
+                if (j0 < a.ldu) uf[c] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(urow) + j0);
+            }
+        }
+    }
+    for (int i = tid; i < kTopkBins; i += NT) hist[i] = 0;
+
+    uint32_t key[NCH][4];
+    int npos = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool in = c * CHUNK + tid * 4 + e < F;
+            key[c][e] = in ? float_key(gv[c][e]) : 0u;       // padding gets the smallest key ...
+            npos += (in && (key[c][e] >> 31)) ? 1 : 0;
+        }
+    // ---- sign digit: keys with the top bit set are the non-negative values
+    npos = (int)wave_sum((float)npos);                       // exact: counts are far below 2^24
+    if (lane == 0) red[wave] = npos;
+    __syncthreads();
+    int total_pos = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) total_pos += red[w];
+    uint32_t prefix = total_pos >= K ? 1u : 0u;              // leading bit of the K-th largest key
+    int need = total_pos >= K ? K : K - total_pos;
+    __syncthreads();
+
+    // ---- three histogram passes over bits [30:21], [20:10], [9:0]
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+        const int nbits = pass == 1 ? 11 : 10;
+        const int nbins = 1 << nbits;
+        const int pshift = shift + nbits;
+        if (pass > 0) {
+            for (int i = tid; i < kTopkBins; i += NT) hist[i] = 0;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t k = key[c][e];
+                const bool in = c * CHUNK + tid * 4 + e < F;
+                if (in && (k >> pshift) == prefix) atomicAdd(&hist[(k >> shift) & (nbins - 1)], 1u);
+            }
+        __syncthreads();
+        const int per = (nbins + NT - 1) / NT;
+        int local = 0;
+        for (int q = 0; q < per; ++q) {
+            const int b = nbins - 1 - (tid * per + q);
+            if (b >= 0) local += (int)hist[b];
+        }
+        int total;
+        const int above = block_exclusive_scan<NT>(local, red, &total);
+        if (above < need && above + local >= need) {
+            int run = above;
+            for (int q = 0; q < per; ++q) {
+                const int b = nbins - 1 - (tid * per + q);
+                if (b < 0) break;
+                const int h = (int)hist[b];
+                if (run + h >= need) {
+                    sh_prefix = (prefix << nbits) | (uint32_t)b;
+                    sh_need = need - run;
+                    break;
+                }
+                run += h;
+            }
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        __syncthreads();
+    }
+    const uint32_t tau = prefix;
+
+    // ---- ordered counts per (chunk, wave)
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        int ngt = 0, neq = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool in = c * CHUNK + tid * 4 + e < F;
+            ngt += __popcll(__ballot(in && key[c][e] > tau));
+            neq += __popcll(__ballot(in && key[c][e] == tau));
+        }
+        if (lane == 0) {
+            cnt_gt[c * NW + wave] = ngt;
+            cnt_eq[c * NW + wave] = neq;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        constexpr int n = NCH * NW;
+        constexpr int per = (n + 63) / 64;
+        int sg = 0, se = 0;
+#pragma unroll
+        for (int q = 0; q < per; ++q) {
+            const int i = lane * per + q;
+            if (i < n) { sg += cnt_gt[i]; se += cnt_eq[i]; }
+        }
+        int ig = sg, ie = se;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int tg = __shfl_up(ig, o, 64), te = __shfl_up(ie, o, 64);
+            if (lane >= o) { ig += tg; ie += te; }
+        }
+        int rg = ig - sg, re = ie - se;
+#pragma unroll
+        for (int q = 0; q < per; ++q) {
+            const int i = lane * per + q;
+            if (i < n) {
+                const int g0 = cnt_gt[i], e0 = cnt_eq[i];
+                cnt_gt[i] = rg; cnt_eq[i] = re;
+                rg += g0; re += e0;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- rank and write
+    int32_t* idx_row = a.idx + row * K;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int j0 = c * CHUNK + tid * 4;
+        int gt_before = cnt_gt[c * NW + wave], eq_before = cnt_eq[c * NW + wave];
+        bool isgt[4], iseq[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool in = j0 + e < F;
+            isgt[e] = in && key[c][e] > tau;
+            iseq[e] = in && key[c][e] == tau;
+            gt_before += mbcnt(__ballot(isgt[e]));
+            eq_before += mbcnt(__ballot(iseq[e]));
+        }
+        float z[4], uu[4];
+        if (FUSED) {
+            if (sizeof(E) == 2) {
+                uu[0] = __uint_as_float(uraw[c][0] << 16); uu[1] = __uint_as_float(uraw[c][0] & 0xFFFF0000u);
+                uu[2] = __uint_as_float(uraw[c][1] << 16); uu[3] = __uint_as_float(uraw[c][1] & 0xFFFF0000u);
+            } else {
+                uu[0] = uf[c][0]; uu[1] = uf[c][1]; uu[2] = uf[c][2]; uu[3] = uf[c][3];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool sel = isgt[e] || (iseq[e] && eq_before < need);
+            z[e] = 0.0f;
+            if (sel) {
+                const int slot = gt_before + min(eq_before, need);
+                const float g = key_float(key[c][e]);
+                idx_row[slot] = j0 + e;
+                if (a.gsel_f32) a.gsel_f32[row * K + slot] = g;
+                if (a.gvals) Elem<E>::store(a.gvals + row * K + slot, g);
+                if (FUSED) {
+                    Elem<E>::store(a.uvals + row * K + slot, uu[e]);
+                    z[e] = silu_f32(g) * uu[e];
+                }
+            }
+            gt_before += isgt[e] ? 1 : 0;
+            eq_before += iseq[e] ? 1 : 0;
+        }
+        if (FUSED && j0 < a.ldz) store_vec4_any<E>(a.zd + row * a.ldz + j0, z);
     }
 }
 
