@@ -85,6 +85,9 @@ template <class E, bool DENSE> struct EpiBwdPointwise {
     E* dud;  // [T, ldf]
     int F;
     int64_t ldf;
+    // Branch-free on purpose: the stored values of all four channels are loaded unconditionally
+    // (clamped slot, always a valid address) and masked afterwards, so the loads of several calls
+    // can be in flight together instead of forming a chain of dependent, predicated gathers.
     __device__ __forceinline__ void store4(int t, int j0, const float v[4]) const {
         if (j0 >= ldf) return;
         float z[4], dg[4], du[4];
@@ -99,15 +102,23 @@ template <class E, bool DENSE> struct EpiBwdPointwise {
             bits = (w >> sh) & 0xFu;
             slot = (int)pref[(int64_t)t * nw + wi] + __popc(w & ((1u << sh) - 1u));
         }
+        const E* grow = gvals + (int64_t)t * K;
+        const E* urow = uvals + (int64_t)t * K;
+        float g[4], u[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            z[r] = dg[r] = du[r] = 0.0f;
-            if (j0 + r < F && ((bits >> r) & 1u)) {
-                const float g = Elem<E>::load(gvals + (int64_t)t * K + slot);
-                const float u = Elem<E>::load(uvals + (int64_t)t * K + slot);
-                moc_bwd_pointwise(g, u, v[r], z[r], dg[r], du[r]);
-                ++slot;
-            }
+            const int sl = min(slot + __popc(bits & ((1u << r) - 1u)), K - 1);
+            g[r] = Elem<E>::load(grow + sl);
+            u[r] = Elem<E>::load(urow + sl);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool on = j0 + r < F && ((bits >> r) & 1u);
+            float zz, gg, uu;
+            moc_bwd_pointwise(g[r], u[r], v[r], zz, gg, uu);
+            z[r] = on ? zz : 0.0f;
+            dg[r] = on ? gg : 0.0f;
+            du[r] = on ? uu : 0.0f;
         }
         store_vec4<E>(zd + (int64_t)t * ldf + j0, z);
         store_vec4<E>(dgd + (int64_t)t * ldf + j0, dg);

@@ -298,9 +298,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             constexpr int LPR = WN / 4;                            // lanes per staged row
             constexpr int RPI = 64 / LPR;                          // rows per instruction
-#pragma unroll 1
+#pragma unroll 4
             for (int it = 0; it < 32 / RPI; ++it) {
                 const int row = it * RPI + lane / LPR, c4 = lane % LPR;
+                if (64 % LPR != 0 && lane >= RPI * LPR) continue;    // lanes beyond the last whole row
                 const f32x4_t t = *reinterpret_cast<const f32x4_t*>(area + row * EPITCH + c4 * 16);
                 const int m = m0 + wm0 + i * 32 + row;
                 const float v[4] = {t[0], t[1], t[2], t[3]};

@@ -115,7 +115,7 @@ int env_int(const char* name, int dflt) {
 
 struct Options {
     int force_generic;   // MOC_FORCE_GENERIC=1: never use the MFMA GEMM
-    int tile;            // MOC_GEMM_TILE=256|128|0 (0 = choose by problem size)
+    int tile;            // MOC_GEMM_TILE=256|192|128 forces a tile shape, 0 = choose by problem size
     Options() : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)) {}
 };
 const Options& options() {
@@ -164,12 +164,22 @@ moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, 
     Span span(name, st);
     if constexpr (std::is_same<E, bf16_t>::value) {
         if (!options().force_generic && mfma_problem_ok(pr)) {
-            int tile = options().tile;
-            if (tile == 0) {
-                const int64_t t256 = (int64_t)((pr.M + 255) / 256) * ((pr.N + 255) / 256);
-                tile = t256 >= 128 ? 256 : 128;
+            // tile shape: fewest rounds of workgroups over the 256 CUs, weighted by tile area and a
+            // small efficiency penalty for the smaller shapes
+            struct Cand { int bm, bn; double penalty; };
+            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.06}, {128, 128, 1.3}};
+            int best = 0;
+            double best_cost = 0.0;
+            for (int c = 0; c < 3; ++c) {
+                const int64_t tiles = (int64_t)((pr.M + cands[c].bm - 1) / cands[c].bm) * ((pr.N + cands[c].bn - 1) / cands[c].bn);
+                const double cost = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn * cands[c].penalty;
+                if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
             }
-            hipError_t e = tile == 256 ? launch_mfma_tail<256, 256, AKM, BKM, Epi>(pr, epi, st)
+            if (options().tile == 256) best = 0;
+            if (options().tile == 192) best = 1;
+            if (options().tile == 128) best = 2;
+            hipError_t e = best == 0   ? launch_mfma_tail<256, 256, AKM, BKM, Epi>(pr, epi, st)
+                           : best == 1 ? launch_mfma_tail<256, 192, AKM, BKM, Epi>(pr, epi, st)
                                        : launch_mfma_tail<128, 128, AKM, BKM, Epi>(pr, epi, st);
             if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
             return MOC_OK;
