@@ -32,7 +32,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--calibrate-traffic", action="store_true",
+                    help="run only moc_residual_add on 2 x 512 MiB (known traffic: 1 GiB read, 512 MiB written per "
+                         "launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
     return ap.parse_args()
 
 
@@ -70,6 +73,15 @@ def main():
     moc.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_traffic:
+        n_rows, n_cols = 65536, 4096                       # 512 MiB of bf16 per array
+        h = torch.zeros((n_rows, n_cols), dtype=torch.bfloat16, device=dev)
+        yv = torch.ones((n_rows, n_cols), dtype=torch.bfloat16, device=dev)
+        for _ in range(4):
+            moc.moc_residual_add(h, yv)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "moc_residual_add", "read_bytes": 2 * h.numel() * 2, "write_bytes": h.numel() * 2}))
+        return
     cfg = CONFIGS[args.workload]
     cfg_index = int(args.workload[-1])
     T, d, F, K = cfg.T, cfg.d, cfg.F, cfg.K
@@ -123,12 +135,22 @@ def main():
             row["algorithmic_tflops"] = round(al / (avg_ms * 1e-3) / 1e12, 2)
             row["frac_executed"] = round(row["executed_tflops"] / PEAK_BF16_TFLOPS, 4)
         kernels.append(row)
+    # roofline entry: the gate GEMM, the one contraction whose algorithmic FLOPs (2 d F per token)
+    # equal the executed ones.  HBM traffic per launch comes from the committed rocprofv3 counter
+    # summary (profiles/), not from this run.
     gate = next((r for r in kernels if r["kernel"] == "gemm_gate"), None)
     roofline = None
     if gate:
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "cfg2_traffic.json")
+        if args.workload == "cfg2" and os.path.exists(tpath):
+            tj = json.load(open(tpath))
+            ent = tj.get("gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>")
+            if ent:
+                traffic = ent["hbm_read_bytes"] + ent["hbm_written_bytes"]
         roofline = {"kernel": "gemm_gate", "bound": "mfma", "achieved": gate["executed_tflops"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(gate["executed_tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                    "avg_ms": gate["avg_ms"]}
+                    "unit": "TFLOP/s", "frac": round(gate["executed_tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                    "avg_ms": gate["avg_ms"], "flops_per_launch": flops["gemm_gate"][1]}
     gemm_ms = sum(r["avg_ms"] for r in kernels if r["kernel"] in flops)
     gemm_ex = sum(flops[r["kernel"]][0] for r in kernels if r["kernel"] in flops)
     gemm_al = sum(flops[r["kernel"]][1] for r in kernels if r["kernel"] in flops)
@@ -216,6 +238,16 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
         torch.cuda.synchronize()
         us = sorted(s.elapsed_time(e) * 1e3 for s, e in zip(start, stop))
         med = us[len(us) // 2]
+        # per-kernel durations of the cold calls (library-side HIP events, separate pass)
+        moc.timing_reset()
+        moc.timing_enable(True)
+        for i in range(2 * R):
+            r = i % R
+            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+        torch.cuda.synchronize()
+        kern_us = {k: round(ms * 1e3 / max(n, 1), 2) for k, (ms, n) in moc.timing_read().items()}
+        moc.timing_enable(False)
+        moc.timing_reset()
         # warm: the same weight set every call (cache-resident, reported separately)
         for _ in range(3):
             moc.moc_ffn_decode(xs[0], *sets[0], K, ws=ws, out=(y, idx))
@@ -230,7 +262,8 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
         gbs = algo_bytes / (med * 1e-6) / 1e9
         out.append({"B": B, "cold_us_median": round(med, 2), "cold_us_min": round(us[0], 2), "warm_us": round(warm_us, 2),
                     "union_channels": round(union, 1), "algorithmic_MB": round(algo_bytes / 1e6, 2),
-                    "effective_GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
+                    "effective_GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+                    "kernels_us": kern_us})
     return {"workload": "cfg3: d_model=%d d_ff=%d K=%d bf16, cold weights (8 rotating sets)" % (d, F, K), "batches": out}
 
 

@@ -12,20 +12,25 @@ namespace moc {
 template <class E> struct Chunk;   // 16 bytes of E as floats
 template <> struct Chunk<float> {
     static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(u32x4_t t, float* v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(t[i]);
+    }
     static __device__ __forceinline__ void load(const float* p, float* v) {
-        f32x4_t t = *reinterpret_cast<const f32x4_t*>(p);
-        v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+        unpack(*reinterpret_cast<const u32x4_t*>(p), v);
     }
 };
 template <> struct Chunk<bf16_t> {
     static constexpr int N = 8;
-    static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
-        u32x4_t t = *reinterpret_cast<const u32x4_t*>(p);
+    static __device__ __forceinline__ void unpack(u32x4_t t, float* v) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             v[2 * i] = __uint_as_float(t[i] << 16);
             v[2 * i + 1] = __uint_as_float(t[i] & 0xFFFF0000u);
         }
+    }
+    static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
+        unpack(*reinterpret_cast<const u32x4_t*>(p), v);
     }
 };
 
@@ -46,20 +51,34 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nwave = gridDim.x * 4;
+    constexpr int UN = 8;      // 16-byte chunks of the row in flight per lane
     for (int j = wave; j < F; j += nwave) {
         const E* wrow = wg + (int64_t)j * d;
         float acc[BT];
 #pragma unroll
         for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
-        for (int k = lane * CN; k < d; k += 64 * CN) {
-            float w[CN];
-            Chunk<E>::load(wrow + k, w);
+        for (int k0 = lane * CN; k0 < d; k0 += 64 * CN * UN) {
+            u32x4_t raw[UN];
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                float xv[CN];
-                Chunk<E>::load(xs + b * d + k, xv);
+            for (int u = 0; u < UN; ++u) {
+                const int k = k0 + u * 64 * CN;
+                raw[u] = u32x4_t{0, 0, 0, 0};
+                if (k < d) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + k));
+            }
 #pragma unroll
-                for (int e = 0; e < CN; ++e) acc[b] = fmaf(w[e], xv[e], acc[b]);
+            for (int u = 0; u < UN; ++u) {
+                const int k = k0 + u * 64 * CN;
+                if (k < d) {
+                    float w[CN];
+                    Chunk<E>::unpack(raw[u], w);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        float xv[CN];
+                        Chunk<E>::load(xs + b * d + k, xv);
+#pragma unroll
+                        for (int e = 0; e < CN; ++e) acc[b] = fmaf(w[e], xv[e], acc[b]);
+                    }
+                }
             }
         }
 #pragma unroll
@@ -146,14 +165,114 @@ __global__ __launch_bounds__(256) void decode_down_kernel(const E* __restrict__ 
     }
 }
 
-// y[b, c] = sum_p part[p, b, c], fixed order (deterministic).
-template <class E>
-__global__ void decode_reduce_kernel(const float* __restrict__ part, int P, int64_t n, E* __restrict__ y) {
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0.0f;
-        for (int p = 0; p < P; ++p) s += part[(int64_t)p * n + i];
-        Elem<E>::store(y + i, s);
+// Fused gather stage for one token per workgroup column: for the p-th share of token b's selected
+// channels, u = x[b] . wu[j], z' = SiLU(g) u, and part[p, b, :] = sum z' wd[j, :].  A wavefront
+// owns a channel at a time and has both of its rows (one of wu, one of wd, NIT 16-byte chunks per
+// lane each) in flight before it waits.  grid = (P, B), 512 threads; needs d <= 64 * CN * NIT.
+template <class E, int NIT>
+__global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict__ x, const E* __restrict__ wu,
+                                                            const E* __restrict__ wd,
+                                                            const int32_t* __restrict__ idx,
+                                                            const float* __restrict__ gsel, int d, int K, int P,
+                                                            float* __restrict__ part) {
+    constexpr int CN = Chunk<E>::N;
+    constexpr int NWV = 8;
+    extern __shared__ __align__(16) unsigned char dec_smem[];
+    E* xs = reinterpret_cast<E*>(dec_smem);
+    float* red = reinterpret_cast<float*>(dec_smem + (size_t)d * sizeof(E));     // [NWV][d]
+    const int p = blockIdx.x, b = blockIdx.y;
+    for (int i = threadIdx.x * CN; i < d; i += 512 * CN)
+        *reinterpret_cast<u32x4_t*>(xs + i) = *reinterpret_cast<const u32x4_t*>(x + (int64_t)b * d + i);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per = (K + P - 1) / P;
+    const int s_begin = p * per, s_end = min(K, s_begin + per);
+    float acc[NIT][CN];
+#pragma unroll
+    for (int i = 0; i < NIT; ++i)
+#pragma unroll
+        for (int e = 0; e < CN; ++e) acc[i][e] = 0.0f;
+    for (int s = s_begin + wave; s < s_end; s += NWV) {
+        const int j = idx[(int64_t)b * K + s];
+        const float gj = gsel[(int64_t)b * K + s];
+        const E* urow = wu + (int64_t)j * d;
+        const E* drow = wd + (int64_t)j * d;
+        u32x4_t ru[NIT], rd[NIT];
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int k = i * 64 * CN + lane * CN;
+            ru[i] = u32x4_t{0, 0, 0, 0};
+            if (k < d) ru[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(urow + k));
+        }
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int k = i * 64 * CN + lane * CN;
+            rd[i] = u32x4_t{0, 0, 0, 0};
+            if (k < d) rd[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(drow + k));
+        }
+        float dot = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int k = i * 64 * CN + lane * CN;
+            if (k < d) {
+                float w[CN], xv[CN];
+                Chunk<E>::unpack(ru[i], w);
+                Chunk<E>::load(xs + k, xv);
+#pragma unroll
+                for (int e = 0; e < CN; ++e) dot = fmaf(w[e], xv[e], dot);
+            }
+        }
+        dot = wave_sum(dot);
+        const float zz = silu_f32(gj) * dot;
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            float w[CN];
+            Chunk<E>::unpack(rd[i], w);
+#pragma unroll
+            for (int e = 0; e < CN; ++e) acc[i][e] = fmaf(zz, w[e], acc[i][e]);
+        }
     }
+#pragma unroll
+    for (int i = 0; i < NIT; ++i) {
+        const int k = i * 64 * CN + lane * CN;
+        if (k < d) {
+#pragma unroll
+            for (int e = 0; e < CN; ++e) red[wave * d + k + e] = acc[i][e];
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += 512) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) s += red[w * d + c];
+        part[((int64_t)p * gridDim.y + b) * d + c] = s;
+    }
+}
+
+// y[b, c] = sum_p part[p, b, c] in a fixed order (deterministic).  A 256-thread workgroup owns 64
+// columns; its four wavefronts each sum a quarter of the P partials with several loads in flight
+// and the quarters are combined through LDS.
+template <class E>
+__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part, int P, int64_t n,
+                                                            E* __restrict__ y) {
+    __shared__ float red[4][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+    const int per = (P + 3) / 4;
+    const int p0 = q * per, p1 = min(P, p0 + per);
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    if (c < n) {
+        int p = p0;
+        for (; p + 3 < p1; p += 4) {
+            const float a0 = part[(int64_t)p * n + c], a1 = part[(int64_t)(p + 1) * n + c];
+            const float a2 = part[(int64_t)(p + 2) * n + c], a3 = part[(int64_t)(p + 3) * n + c];
+            s0 += a0; s1 += a1; s2 += a2; s3 += a3;
+        }
+        for (; p < p1; ++p) s0 += part[(int64_t)p * n + c];
+    }
+    red[q][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (q == 0 && c < n) Elem<E>::store(y + c, (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]));
 }
 
 }  // namespace moc

@@ -278,9 +278,12 @@ template <class E> struct BwdWs {      // selection bit mask and the three dense
     }
 };
 
-int decode_splits(int B) {
-    int P = 128 / B;
-    return P < 8 ? 8 : (P > 64 ? 64 : P);
+// Channel shares per token in the gather stage: about one channel per wavefront (8 per workgroup)
+// for the smallest batches, fewer and longer shares as the batch grows.
+int decode_splits(int B, int K) {
+    const int by_batch = B <= 2 ? 256 : (B <= 4 ? 96 : (B <= 8 ? 48 : 24));
+    const int by_k = (K + 7) / 8;
+    return std::max(1, std::min(by_batch, by_k));
 }
 
 struct DecodeWs {
@@ -293,7 +296,7 @@ struct DecodeWs {
         gsel = c.take<float>((size_t)D.T * D.K);
         z = c.take<float>((size_t)D.T * D.K);
         idx = c.take<int32_t>((size_t)D.T * D.K);
-        part = c.take<float>((size_t)decode_splits(D.T) * D.T * D.d);
+        part = c.take<float>((size_t)decode_splits(D.T, D.K) * D.T * D.d);
         bytes = c.off;
     }
 };
@@ -411,16 +414,29 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     if (s != MOC_OK) return s;
     TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
     if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
-    {
-        const size_t lds = (size_t)D.d * sizeof(E);
-        if (lds > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
-        Span span("decode_up", st);
-        const int gx = std::max(1, std::min((D.K + 3) / 4, 1024 / B));
-        hipLaunchKernelGGL((decode_up_kernel<E>), dim3(gx, B), dim3(256), lds, st, x, wu, idx, W.gsel, D.d, D.K, W.z);
+    const int P = decode_splits(B, D.K);
+    constexpr int NIT = 8;
+    const size_t fused_lds = (size_t)D.d * sizeof(E) + (size_t)8 * D.d * sizeof(float);
+    if (D.d <= 64 * Chunk<E>::N * NIT && fused_lds <= 160 * 1024 - 64) {
+        auto kern = decode_updown_kernel<E, NIT>;
+        static bool attr = false;
+        if (!attr) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        160 * 1024 - 64));
+            attr = true;
+        }
+        Span span("decode_updown", st);
+        hipLaunchKernelGGL(kern, dim3(P, B), dim3(512), fused_lds, st, x, wu, wd, idx, W.gsel, D.d, D.K, P, W.part);
         HIP_TRY(hipGetLastError());
-    }
-    const int P = decode_splits(B);
-    {
+    } else {
+        {
+            const size_t lds = (size_t)D.d * sizeof(E);
+            if (lds > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
+            Span span("decode_up", st);
+            const int gx = std::max(1, std::min((D.K + 3) / 4, 1024 / B));
+            hipLaunchKernelGGL((decode_up_kernel<E>), dim3(gx, B), dim3(256), lds, st, x, wu, idx, W.gsel, D.d, D.K, W.z);
+            HIP_TRY(hipGetLastError());
+        }
         Span span("decode_down", st);
         constexpr int SLICE = 64 * Chunk<E>::N * 4;
         hipLaunchKernelGGL((decode_down_kernel<E, 4>), dim3(P, B, (D.d + SLICE - 1) / SLICE), dim3(256), 0, st, wd, idx,
@@ -430,7 +446,7 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     {
         Span span("decode_reduce", st);
         const int64_t n = (int64_t)B * D.d;
-        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, W.part, P, n,
+        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, W.part, P, n,
                            y);
         HIP_TRY(hipGetLastError());
     }
