@@ -89,6 +89,84 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
     }
 }
 
+// Gate projection for batches of 5..16 tokens on the matrix cores (bf16 only):
+//   g[b, j] = x[b] . wg[j]  as D[row j][token b] tiles of v_mfma_f32_16x16x32_bf16.
+// A 768-thread workgroup owns 48 consecutive channel rows (230 workgroups for 11008 rows, one per
+// CU): wave w works on row group w / 4 (16 rows) and on the quarter w % 4 of the contraction, so
+// 12 waves keep 12 x 8 KB of weights in flight per CU.  Lane l of a wave reads 32 contiguous bytes of row l % 16 per step (4 lanes cover
+// a 128-byte line); x[16, d] sits in LDS (rows padded by 16 bytes) and supplies the second MFMA
+// input with the same k assignment.  The four partial tiles of a row group are summed through LDS.
+// Needs d % 1024 == 0 (every wave's share is a whole number of 4-step prefetch groups).
+typedef __bf16 dec_bf16x8_t __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __restrict__ x,
+                                                                const bf16_t* __restrict__ wg, int B, int d, int F,
+                                                                float* __restrict__ g, int64_t ldg) {
+    extern __shared__ __align__(16) unsigned char dec_smem[];
+    const int xpitch = d * 2 + 16;                                   // bytes per staged token row
+    float* red = reinterpret_cast<float*>(dec_smem + 16 * xpitch);   // [3 row groups][4 quarters][256]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rg = wave >> 2, ks = wave & 3;
+    const int row0 = blockIdx.x * 48 + rg * 16;
+    const int kq = d / 4;                                            // contraction share of this wave
+    const int q = lane >> 4;                                         // 16-element k sub-block of a 64-wide step
+    const bf16_t* wrow = wg + (int64_t)min(row0 + (lane & 15), F - 1) * d + ks * kq + q * 16;
+    // first weights in flight before x is staged
+    constexpr int UN = 4;                                            // steps of 64 k in flight
+    u32x4_t w0[UN], w1[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+        w0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + u * 64));
+        w1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + u * 64 + 8));
+    }
+    for (int i = tid * 8; i < 16 * d; i += 768 * 8) {
+        const int b = i / d, k = i - b * d;
+        u32x4_t v = {0, 0, 0, 0};
+        if (b < B) v = *reinterpret_cast<const u32x4_t*>(x + i);
+        *reinterpret_cast<u32x4_t*>(dec_smem + b * xpitch + k * 2) = v;
+    }
+    __syncthreads();
+    const unsigned char* xl = dec_smem + (lane & 15) * xpitch + (ks * kq + q * 16) * 2;
+    f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int nstep = kq / 64;
+    for (int s0 = 0; s0 < nstep; s0 += UN) {
+        u32x4_t c0[UN], c1[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) { c0[u] = w0[u]; c1[u] = w1[u]; }
+        const int nxt = min(s0 + UN, nstep - UN);                    // clamped prefetch of the next UN steps
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            w0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64));
+            w1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64 + 8));
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            if (s0 + u < nstep) {
+                const dec_bf16x8_t x0 = *reinterpret_cast<const dec_bf16x8_t*>(xl + (s0 + u) * 128);
+                const dec_bf16x8_t x1 = *reinterpret_cast<const dec_bf16x8_t*>(xl + (s0 + u) * 128 + 16);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c0[u]), x0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c1[u]), x1, acc, 0, 0, 0);
+            }
+        }
+    }
+    // acc[r] = D[row 4*(lane/16) + r][token lane % 16] over this wave's quarter of k
+    *reinterpret_cast<f32x4_t*>(red + ((rg * 4 + ks) * 64 + lane) * 4) = acc;
+    __syncthreads();
+    if (ks == 0) {
+        f32x4_t s = acc;
+#pragma unroll
+        for (int o = 1; o < 4; ++o) s += *reinterpret_cast<const f32x4_t*>(red + ((rg * 4 + o) * 64 + lane) * 4);
+        const int b = lane & 15, r = row0 + 4 * (lane >> 4);
+        if (b < B) {
+            if (r + 3 < F) *reinterpret_cast<f32x4_t*>(g + (int64_t)b * ldg + r) = s;
+            else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (r + e < F) g[(int64_t)b * ldg + r + e] = s[e];
+            }
+        }
+    }
+}
+
 // z[b, s] = SiLU(gsel[b, s]) * (x[b] . wu[idx[b, s]])  for every selected (token, channel) pair.
 // grid = (row groups, B); x[b] is staged in LDS.
 template <class E>
@@ -181,9 +259,6 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
     E* xs = reinterpret_cast<E*>(dec_smem);
     float* red = reinterpret_cast<float*>(dec_smem + (size_t)d * sizeof(E));     // [NWV][d]
     const int p = blockIdx.x, b = blockIdx.y;
-    for (int i = threadIdx.x * CN; i < d; i += 512 * CN)
-        *reinterpret_cast<u32x4_t*>(xs + i) = *reinterpret_cast<const u32x4_t*>(x + (int64_t)b * d + i);
-    __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per = (K + P - 1) / P;
     const int s_begin = p * per, s_end = min(K, s_begin + per);
@@ -192,12 +267,14 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
     for (int i = 0; i < NIT; ++i)
 #pragma unroll
         for (int e = 0; e < CN; ++e) acc[i][e] = 0.0f;
-    for (int s = s_begin + wave; s < s_end; s += NWV) {
+    u32x4_t ru[NIT], rd[NIT];
+    float gj = 0.0f;
+    // rows of channel slot s (both matrices) -> registers; all loads are issued before any is used
+    auto fetch_rows = [&](int s) {
         const int j = idx[(int64_t)b * K + s];
-        const float gj = gsel[(int64_t)b * K + s];
+        gj = gsel[(int64_t)b * K + s];
         const E* urow = wu + (int64_t)j * d;
         const E* drow = wd + (int64_t)j * d;
-        u32x4_t ru[NIT], rd[NIT];
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int k = i * 64 * CN + lane * CN;
@@ -210,6 +287,13 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
             rd[i] = u32x4_t{0, 0, 0, 0};
             if (k < d) rd[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(drow + k));
         }
+    };
+    int s = s_begin + wave;
+    if (s < s_end) fetch_rows(s);          // in flight while x is staged
+    for (int i = threadIdx.x * CN; i < d; i += 512 * CN)
+        *reinterpret_cast<u32x4_t*>(xs + i) = *reinterpret_cast<const u32x4_t*>(x + (int64_t)b * d + i);
+    __syncthreads();
+    while (s < s_end) {
         float dot = 0.0f;
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
@@ -231,6 +315,8 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
 #pragma unroll
             for (int e = 0; e < CN; ++e) acc[i][e] = fmaf(zz, w[e], acc[i][e]);
         }
+        s += NWV;
+        if (s < s_end) fetch_rows(s);
     }
 #pragma unroll
     for (int i = 0; i < NIT; ++i) {
@@ -249,16 +335,16 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
     }
 }
 
-// y[b, c] = sum_p part[p, b, c] in a fixed order (deterministic).  A 256-thread workgroup owns 64
-// columns; its four wavefronts each sum a quarter of the P partials with several loads in flight
-// and the quarters are combined through LDS.
+// y[b, c] = sum_p part[p, b, c] in a fixed order (deterministic).  A 1024-thread workgroup owns 64
+// columns; its sixteen wavefronts each sum a sixteenth of the P partials with the loads in flight
+// together, and the sixteen sums are combined through LDS.
 template <class E>
-__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part, int P, int64_t n,
-                                                            E* __restrict__ y) {
-    __shared__ float red[4][64];
+__global__ __launch_bounds__(1024) void decode_reduce_kernel(const float* __restrict__ part, int P, int64_t n,
+                                                             E* __restrict__ y) {
+    __shared__ float red[16][64];
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int64_t c = (int64_t)blockIdx.x * 64 + lane;
-    const int per = (P + 3) / 4;
+    const int per = (P + 15) / 16;
     const int p0 = q * per, p1 = min(P, p0 + per);
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
     if (c < n) {
@@ -272,7 +358,12 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
     }
     red[q][lane] = (s0 + s1) + (s2 + s3);
     __syncthreads();
-    if (q == 0 && c < n) Elem<E>::store(y + c, (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]));
+    if (q == 0 && c < n) {
+        float t = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w][lane];
+        Elem<E>::store(y + c, t);
+    }
 }
 
 }  // namespace moc

@@ -410,7 +410,26 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     moc_status s;
     if (B == 1) s = decode_gate<E, 1>(D, x, wg, W.g, st);
     else if (B <= 4) s = decode_gate<E, 4>(D, x, wg, W.g, st);
-    else s = decode_gate<E, 16>(D, x, wg, W.g, st);
+    else {
+        const size_t mfma_lds = (size_t)16 * (D.d * 2 + 16) + 4 * 4 * 256 * sizeof(float);
+        if (std::is_same<E, bf16_t>::value && D.d % 1024 == 0 && mfma_lds <= 160 * 1024 - 64 &&
+            !options().force_generic) {
+            static bool attr = false;
+            if (!attr) {
+                HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_gate_mfma_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64));
+                attr = true;
+            }
+            Span span("decode_gate", st);
+            hipLaunchKernelGGL(decode_gate_mfma_kernel, dim3((D.F + 47) / 48), dim3(768), mfma_lds, st,
+                               reinterpret_cast<const bf16_t*>(x), reinterpret_cast<const bf16_t*>(wg), B, D.d, D.F, W.g,
+                               (int64_t)D.ldF);
+            HIP_TRY(hipGetLastError());
+            s = MOC_OK;
+        } else {
+            s = decode_gate<E, 16>(D, x, wg, W.g, st);
+        }
+    }
     if (s != MOC_OK) return s;
     TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
     if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
@@ -446,7 +465,7 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     {
         Span span("decode_reduce", st);
         const int64_t n = (int64_t)B * D.d;
-        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, W.part, P, n,
+        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 63) / 64)), dim3(1024), 0, st, W.part, P, n,
                            y);
         HIP_TRY(hipGetLastError());
     }

@@ -228,7 +228,7 @@ def test_cfg3_decode_7b_shape(B):
 
 
 @pytest.mark.parametrize("B,d,F,K,dtype", [(3, 64, 100, 9, "bf16"), (16, 256, 515, 64, "bf16"), (2, 36, 50, 50, "f32"),
-                                           (7, 512, 1376, 172, "f32")])
+                                           (7, 512, 1376, 172, "f32"), (9, 1024, 333, 40, "bf16"), (16, 2048, 1000, 125, "bf16")])
 def test_decode_small_shapes(B, d, F, K, dtype):
     run_decode_case("small", 94, B, d, F, K, dtype)
 
