@@ -48,6 +48,7 @@ def gemm_flops(T, d, F, K):
         "gemm_up": (ex, al),
         "gemm_down": (ex, al),
         "gemm_dz_pointwise": (ex, al),
+        "gemm_dz": (ex, al),
         "gemm_dwd": (ex, al),
         "gemm_dwg": (ex, al),
         "gemm_dwu": (ex, al),

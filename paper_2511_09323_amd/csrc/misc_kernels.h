@@ -1,5 +1,5 @@
-// Small bandwidth-bound kernels around the GEMMs: the selection bit mask for the backward,
-// RMSNorm and the residual add.
+// Small bandwidth-bound kernels around the GEMMs: the backward's pointwise/expansion step, the
+// selection bit mask of its fallback, RMSNorm and the residual add.
 #pragma once
 #include "common.h"
 
@@ -46,6 +46,55 @@ __global__ __launch_bounds__(256) void build_mask_kernel(const int32_t* __restri
             pref[t * nw + i] = (uint16_t)run;
             run += __popc(w);
         }
+    }
+}
+
+// Backward pointwise step on the compact stored set, expanded to the dense operands of the
+// weight-gradient and dX GEMMs.  One workgroup per token row t: for every stored slot s with channel
+// j = idx[t, s] it takes dz' = dzd[t, j] (the dense dD W_down^T product), recomputes s = SiLU(g),
+// z' = s u and forms du = s dz', dg = u dz' SiLU'(g) (Eqs. bp-1 ... bp-3, S' and Z' recomputed from
+// the stored G.M as in MoC+GCP).  The three rows z', dg, du are assembled in LDS -- zero everywhere
+// except at the K selected channels -- and streamed out with 16-byte stores, padding included.
+template <class E>
+__global__ __launch_bounds__(256) void bwd_expand_kernel(const int32_t* __restrict__ idx, const E* __restrict__ gvals,
+                                                         const E* __restrict__ uvals, const E* __restrict__ dzd,
+                                                         int K, int F, int64_t ldf, E* __restrict__ zd,
+                                                         E* __restrict__ dgd, E* __restrict__ dud) {
+    extern __shared__ __align__(16) unsigned char exp_smem[];
+    E* rz = reinterpret_cast<E*>(exp_smem);
+    E* rg = rz + ldf;
+    E* ru = rg + ldf;
+    const int tid = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    constexpr int PER16 = 16 / sizeof(E);
+    const int nvec = (int)(3 * ldf) / PER16;
+    for (int i = tid; i < nvec; i += 256) reinterpret_cast<u32x4_t*>(exp_smem)[i] = u32x4_t{0, 0, 0, 0};
+    __syncthreads();
+    const E* dzrow = dzd + t * ldf;
+    for (int s = tid; s < K; s += 256) {
+        const int j = idx[t * K + s];
+        if (j < 0 || j >= F) continue;
+        const float g = Elem<E>::load(gvals + t * K + s);
+        const float u = Elem<E>::load(uvals + t * K + s);
+        const float dz = Elem<E>::load(dzrow + j);
+        float z, dg, du;
+        moc_bwd_pointwise(g, u, dz, z, dg, du);
+        Elem<E>::store(rz + j, z);
+        Elem<E>::store(rg + j, dg);
+        Elem<E>::store(ru + j, du);
+    }
+    __syncthreads();
+    const int rowvec = (int)ldf / PER16;
+    u32x4_t* oz = reinterpret_cast<u32x4_t*>(zd + t * ldf);
+    u32x4_t* og = reinterpret_cast<u32x4_t*>(dgd + t * ldf);
+    u32x4_t* ou = reinterpret_cast<u32x4_t*>(dud + t * ldf);
+    const u32x4_t* lz = reinterpret_cast<const u32x4_t*>(rz);
+    const u32x4_t* lg = reinterpret_cast<const u32x4_t*>(rg);
+    const u32x4_t* lu = reinterpret_cast<const u32x4_t*>(ru);
+    for (int i = tid; i < rowvec; i += 256) {
+        oz[i] = lz[i];
+        og[i] = lg[i];
+        ou[i] = lu[i];
     }
 }
 

@@ -262,15 +262,16 @@ template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gat
     }
 };
 
-template <class E> struct BwdWs {      // selection bit mask and the three dense [T, ldF] operands
+template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mask of the fallback path)
     uint32_t* maskw;
     uint16_t* pref;
-    E *Zd, *dGd, *dUd;
+    E *dZd, *Zd, *dGd, *dUd;
     size_t bytes;
     BwdWs(void* ws, const Dims& D, bool dense) {
         Carver c(ws);
         maskw = dense ? nullptr : c.take<uint32_t>((size_t)D.T * D.nw);
         pref = dense ? nullptr : c.take<uint16_t>((size_t)D.T * D.nw);
+        dZd = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
         Zd = c.take<E>((size_t)D.T * D.ldF);
         dGd = c.take<E>((size_t)D.T * D.ldF);
         dUd = c.take<E>((size_t)D.T * D.ldF);
@@ -344,16 +345,34 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                     hipStream_t st) {
     BwdWs<E> W(ws, D, DENSE);
     moc_status s;
-    if (!DENSE) {
-        Span span("build_mask", st);
-        hipLaunchKernelGGL(build_mask_kernel, dim3(D.T), dim3(256), (size_t)D.nw * 4 + 16, st, idx, D.K, D.F, D.nw,
-                           W.maskw, W.pref);
-        HIP_TRY(hipGetLastError());
-    }
-    // dZ' = dD W_down^T (bp-1) with the pointwise part (bp-2, bp-3) in the epilogue
-    EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.Zd, W.dGd, W.dUd, D.F, D.ldF};
     GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0, false};
-    if ((s = run_gemm<E, false, false>("gemm_dz_pointwise", pz, epi, st)) != MOC_OK) return s;
+    const size_t expand_lds = (size_t)3 * D.ldF * sizeof(E);
+    if (!DENSE && expand_lds <= 160 * 1024 - 64) {
+        // dZ' = dD W_down^T (bp-1) stored densely, then the pointwise step (bp-2, bp-3) on the K stored
+        // channels of every token, expanded to the dense-masked rows Z', dG, dU
+        if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
+        auto kern = bwd_expand_kernel<E>;
+        static bool attr = false;
+        if (!attr) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        160 * 1024 - 64));
+            attr = true;
+        }
+        Span span("bwd_pointwise_expand", st);
+        hipLaunchKernelGGL(kern, dim3(D.T), dim3(256), expand_lds, st, idx, gvals, uvals, W.dZd, D.K, D.F,
+                           (int64_t)D.ldF, W.Zd, W.dGd, W.dUd);
+        HIP_TRY(hipGetLastError());
+    } else {
+        if (!DENSE) {
+            Span span("build_mask", st);
+            hipLaunchKernelGGL(build_mask_kernel, dim3(D.T), dim3(256), (size_t)D.nw * 4 + 16, st, idx, D.K, D.F, D.nw,
+                               W.maskw, W.pref);
+            HIP_TRY(hipGetLastError());
+        }
+        // dZ' = dD W_down^T (bp-1) with the pointwise part (bp-2, bp-3) in the epilogue
+        EpiBwdPointwise<E, DENSE> epi{W.maskw, W.pref, D.nw, gvals, uvals, DENSE ? D.F : D.K, W.Zd, W.dGd, W.dUd, D.F, D.ldF};
+        if ((s = run_gemm<E, false, false>("gemm_dz_pointwise", pz, epi, st)) != MOC_OK) return s;
+    }
     // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens,
     // both operands read k-major (token index leading)
     GemmProblem<E> pwd{km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0, false};
