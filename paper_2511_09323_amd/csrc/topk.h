@@ -268,15 +268,20 @@ __global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
 
 // ---------------------------------------------------------------- register-resident variant
 // Row of up to NCH * NT * 4 channels; thread t holds channels c*NT*4 + t*4 .. +3 of every chunk c.
+// Per digit pass there are two barriers: after the histogram atomics, and after wave 0 has scanned
+// the bins (meanwhile the other waves clear the histogram of the next pass).  Channels are ranked
+// with one ballot sweep whose per-lane prefixes stay in registers.  When all keys equal to the
+// threshold are selected (the usual case) a single ">= threshold" predicate is ranked; ties that
+// straddle the cut take the general path with a second predicate.
 template <class E, int NT, int NCH, bool FUSED>
 __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     constexpr int NW = NT / 64;
     constexpr int CHUNK = NT * 4;
-    __shared__ uint32_t hist[kTopkBins];
-    __shared__ int cnt_gt[NCH * NW], cnt_eq[NCH * NW];
+    __shared__ uint32_t hist[2][kTopkBins];
+    __shared__ int tab_gt[NCH * NW], tab_eq[NCH * NW];
     __shared__ int red[NW];
     __shared__ uint32_t sh_prefix;
-    __shared__ int sh_need;
+    __shared__ int sh_need, sh_cnt;
     const int F = a.F, K = a.K;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
@@ -293,8 +298,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             for (int e = 0; e < 4; ++e) gv[c][e] = (j0 + e < F) ? grow[j0 + e] : 0.0f;
         }
     }
-    u32x2_t uraw[NCH];     // FUSED, E = bf16: four packed values; E = float handled below
-    f32x4_t uf[NCH];
+    u32x2_t uraw[NCH];     // FUSED, E = bf16: four packed values
+    f32x4_t uf[NCH];       // FUSED, E = float
     if (FUSED) {
         const E* urow = a.u + row * a.ldu;
 #pragma unroll
@@ -309,7 +314,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             }
         }
     }
-    for (int i = tid; i < kTopkBins; i += NT) hist[i] = 0;
+    for (int i = tid; i < 2 * kTopkBins; i += NT) (&hist[0][0])[i] = 0;
 
     uint32_t key[NCH][4];
     int npos = 0;
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool in = c * CHUNK + tid * 4 + e < F;
-            key[c][e] = in ? float_key(gv[c][e]) : 0u;       // padding gets the smallest key ...
+            key[c][e] = in ? float_key(gv[c][e]) : 0u;
             npos += (in && (key[c][e] >> 31)) ? 1 : 0;
         }
     // ---- sign digit: keys with the top bit set are the non-negative values
@@ -330,7 +335,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     for (int w = 0; w < NW; ++w) total_pos += red[w];
     uint32_t prefix = total_pos >= K ? 1u : 0u;              // leading bit of the K-th largest key
     int need = total_pos >= K ? K : K - total_pos;
-    __syncthreads();
+    int cnt_eq = 0;
 
     // ---- three histogram passes over bits [30:21], [20:10], [9:0]
 #pragma unroll 1
@@ -339,61 +344,79 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         const int nbits = pass == 1 ? 11 : 10;
         const int nbins = 1 << nbits;
         const int pshift = shift + nbits;
-        if (pass > 0) {
-            for (int i = tid; i < kTopkBins; i += NT) hist[i] = 0;
-            __syncthreads();
-        }
+        uint32_t* cur = hist[pass & 1];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const uint32_t k = key[c][e];
                 const bool in = c * CHUNK + tid * 4 + e < F;
-                if (in && (k >> pshift) == prefix) atomicAdd(&hist[(k >> shift) & (nbins - 1)], 1u);
+                if (in && (k >> pshift) == prefix) atomicAdd(&cur[(k >> shift) & (nbins - 1)], 1u);
             }
         __syncthreads();
-        const int per = (nbins + NT - 1) / NT;
-        int local = 0;
-        for (int q = 0; q < per; ++q) {
-            const int b = nbins - 1 - (tid * per + q);
-            if (b >= 0) local += (int)hist[b];
-        }
-        int total;
-        const int above = block_exclusive_scan<NT>(local, red, &total);
-        if (above < need && above + local >= need) {
-            int run = above;
-            for (int q = 0; q < per; ++q) {
-                const int b = nbins - 1 - (tid * per + q);
-                if (b < 0) break;
-                const int h = (int)hist[b];
-                if (run + h >= need) {
-                    sh_prefix = (prefix << nbits) | (uint32_t)b;
-                    sh_need = need - run;
-                    break;
+        if (wave == 0) {
+            // lane l owns bins nbins-1 - l*per .. nbins-1 - l*per - (per-1), i.e. descending order
+            const int per = nbins / 64;
+            int local = 0;
+            for (int q = 0; q < per; ++q) local += (int)cur[nbins - 1 - (lane * per + q)];
+            int inc = local;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += t;
+            }
+            const int above = inc - local;
+            if (above < need && inc >= need) {               // the crossing bin is one of mine
+                int run = above;
+                for (int q = 0; q < per; ++q) {
+                    const int b = nbins - 1 - (lane * per + q);
+                    const int h = (int)cur[b];
+                    if (run + h >= need) {
+                        sh_prefix = (prefix << nbits) | (uint32_t)b;
+                        sh_need = need - run;
+                        sh_cnt = h;
+                        break;
+                    }
+                    run += h;
                 }
-                run += h;
+            }
+        } else if (pass < 2) {
+            uint32_t* nxt = hist[(pass + 1) & 1];
+            if (pass == 1) {                                  // buffer 0 was used by pass 0: clear it again
+                for (int i = tid - 64; i < kTopkBins; i += NT - 64) nxt[i] = 0;
             }
         }
         __syncthreads();
         prefix = sh_prefix;
         need = sh_need;
-        __syncthreads();
+        cnt_eq = sh_cnt;
     }
     const uint32_t tau = prefix;
+    const bool all_ties = cnt_eq == need;        // every key equal to tau is selected
 
-    // ---- ordered counts per (chunk, wave)
+    // ---- one ballot sweep: per-lane prefixes in registers, per-wave totals to LDS
+    int pg[NCH], pe[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        int ngt = 0, neq = 0;
+        int lg = 0, le = 0, ngt = 0, neq = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool in = c * CHUNK + tid * 4 + e < F;
-            ngt += __popcll(__ballot(in && key[c][e] > tau));
-            neq += __popcll(__ballot(in && key[c][e] == tau));
+            const uint32_t k = key[c][e];
+            const uint64_t bg = __ballot(in && (all_ties ? k >= tau : k > tau));
+            lg += mbcnt(bg);
+            ngt += __popcll(bg);
+            if (!all_ties) {
+                const uint64_t be = __ballot(in && k == tau);
+                le += mbcnt(be);
+                neq += __popcll(be);
+            }
         }
+        pg[c] = lg;
+        pe[c] = le;
         if (lane == 0) {
-            cnt_gt[c * NW + wave] = ngt;
-            cnt_eq[c * NW + wave] = neq;
+            tab_gt[c * NW + wave] = ngt;
+            tab_eq[c * NW + wave] = neq;
         }
     }
     __syncthreads();
@@ -404,7 +427,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
 #pragma unroll
         for (int q = 0; q < per; ++q) {
             const int i = lane * per + q;
-            if (i < n) { sg += cnt_gt[i]; se += cnt_eq[i]; }
+            if (i < n) { sg += tab_gt[i]; se += tab_eq[i]; }
         }
         int ig = sg, ie = se;
 #pragma unroll
@@ -417,8 +440,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         for (int q = 0; q < per; ++q) {
             const int i = lane * per + q;
             if (i < n) {
-                const int g0 = cnt_gt[i], e0 = cnt_eq[i];
-                cnt_gt[i] = rg; cnt_eq[i] = re;
+                const int g0 = tab_gt[i], e0 = tab_eq[i];
+                tab_gt[i] = rg; tab_eq[i] = re;
                 rg += g0; re += e0;
             }
         }
@@ -430,16 +453,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int j0 = c * CHUNK + tid * 4;
-        int gt_before = cnt_gt[c * NW + wave], eq_before = cnt_eq[c * NW + wave];
-        bool isgt[4], iseq[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = j0 + e < F;
-            isgt[e] = in && key[c][e] > tau;
-            iseq[e] = in && key[c][e] == tau;
-            gt_before += mbcnt(__ballot(isgt[e]));
-            eq_before += mbcnt(__ballot(iseq[e]));
-        }
+        int gt_before = tab_gt[c * NW + wave] + pg[c];
+        int eq_before = tab_eq[c * NW + wave] + pe[c];
         float z[4], uu[4];
         if (FUSED) {
             if (sizeof(E) == 2) {
@@ -451,11 +466,15 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool sel = isgt[e] || (iseq[e] && eq_before < need);
+            const bool in = j0 + e < F;
+            const uint32_t k = key[c][e];
+            const bool isgt = in && (all_ties ? k >= tau : k > tau);
+            const bool iseq = in && !all_ties && k == tau;
+            const bool sel = isgt || (iseq && eq_before < need);
             z[e] = 0.0f;
             if (sel) {
                 const int slot = gt_before + min(eq_before, need);
-                const float g = key_float(key[c][e]);
+                const float g = key_float(k);
                 idx_row[slot] = j0 + e;
                 if (a.gsel_f32) a.gsel_f32[row * K + slot] = g;
                 if (a.gvals) Elem<E>::store(a.gvals + row * K + slot, g);
@@ -464,8 +483,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                     z[e] = silu_f32(g) * uu[e];
                 }
             }
-            gt_before += isgt[e] ? 1 : 0;
-            eq_before += iseq[e] ? 1 : 0;
+            gt_before += isgt ? 1 : 0;
+            eq_before += iseq ? 1 : 0;
         }
         if (FUSED && j0 < a.ldz) store_vec4_any<E>(a.zd + row * a.ldz + j0, z);
     }
