@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="run only moc_residual_add on 2 x 512 MiB (known traffic: 1 GiB read, 512 MiB written per "
@@ -188,6 +189,11 @@ def main():
     if not args.no_decode:
         decode = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev)
 
+    # prefill-stack leg: one layer of [RMSNorm -> MoC FFN forward -> residual add] at the 7B shape
+    stack = None
+    if not args.no_stack:
+        stack = stack_leg(torch, moc, CONFIGS["cfg4"], dev)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
@@ -200,9 +206,55 @@ def main():
         "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
                    "T": T, "d_model": d, "d_ff": F, "K": K},
         "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
-        "decode": decode,
+        "decode": decode, "prefill_stack_layer": stack,
     }
     print(json.dumps(line))
+
+
+def stack_leg(torch, moc, cfg, dev):
+    """One layer of the cfg4 stack, h <- h + MoC(RMSNorm(h)), timed with its kernels."""
+    from paper_2511_09323_amd.configs import RMSNORM_EPS
+    T, d, F, K = cfg.T, cfg.d, cfg.F, cfg.K
+    bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(40_000)
+    h = torch.randn((T, d), generator=gen, device=dev, dtype=torch.float32).to(bf)
+    w = [(torch.randn((F, d), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(bf) for _ in range(3)]
+    gain = torch.ones((d,), dtype=bf, device=dev)
+    xn = torch.empty_like(h)
+    ws = torch.empty(moc.workspace_bytes(T, d, F, K, bf, 0), dtype=torch.uint8, device=dev)
+    out = (torch.empty((T, d), dtype=bf, device=dev), torch.empty((T, K), dtype=torch.int32, device=dev),
+           torch.empty((T, K), dtype=bf, device=dev), torch.empty((T, K), dtype=bf, device=dev))
+
+    def layer():
+        moc.moc_rmsnorm(h, gain, RMSNORM_EPS, out=xn)
+        y, _, _, _ = moc.moc_ffn_fwd(xn, w[0], w[1], w[2], K, ws=ws, out=out)
+        moc.moc_residual_add(h, y)
+
+    for _ in range(2):
+        layer()
+    torch.cuda.synchronize()
+    n = 5
+    t0 = time.perf_counter()
+    for _ in range(n):
+        layer()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    moc.timing_reset()
+    moc.timing_enable(True)
+    for _ in range(n):
+        layer()
+    torch.cuda.synchronize()
+    kern = {k: round(v / max(c, 1), 4) for k, (v, c) in moc.timing_read().items()}
+    moc.timing_enable(False)
+    moc.timing_reset()
+    ex = 2.0 * T * d * F
+    row_bytes = T * d * 2
+    return {"workload": "cfg4 layer: T=%d d_model=%d d_ff=%d K=%d bf16" % (T, d, F, K), "ms_per_layer": round(ms, 4),
+            "tokens_per_s": round(T / (ms * 1e-3), 1), "ms_32_layers_extrapolated": round(32 * ms, 2), "kernels_ms": kern,
+            "gemm_executed_tflops": {k: round(ex / (kern[k] * 1e-3) / 1e12, 1) for k in ("gemm_gate", "gemm_up", "gemm_down") if k in kern},
+            "rmsnorm_GBs": round(2 * row_bytes / (kern["rmsnorm"] * 1e-3) / 1e9, 1) if "rmsnorm" in kern else None,
+            "residual_add_GBs": round(3 * row_bytes / (kern["residual_add"] * 1e-3) / 1e9, 1) if "residual_add" in kern else None}
 
 
 def decode_leg(torch, moc, inputs, cfg, batches, dev):
