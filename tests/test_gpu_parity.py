@@ -124,6 +124,16 @@ def test_small_ragged_shapes(T, d, F, K, dtype):
     run_fwd_bwd_case("ragged", 90, T, d, F, K, dtype)
 
 
+@pytest.mark.parametrize("T,d,F,K,dtype", [
+    (24, 64, 12000, 1500, "bf16"),    # row too long for registers: LDS-resident fused Top-K
+    (16, 64, 14000, 200, "f32"),      # dense rows too large for the LDS expansion: mask + GEMM-epilogue backward
+    (8, 128, 32768, 4096, "bf16"),    # largest supported d_ff
+    (40, 96, 200, 25, "bf16"),        # contraction tails everywhere (d % 32 != 0, T % 32 != 0, F % 32 != 0)
+])
+def test_fallback_paths_and_limits(T, d, F, K, dtype):
+    run_fwd_bwd_case("limits", 95, T, d, F, K, dtype)
+
+
 def test_cfg1_bf16_forward_backward():
     c = CONFIGS["cfg1"]
     run_fwd_bwd_case("cfg1", 1, c.T, c.d, c.F, c.K, "bf16", expect_window_rows=12)
