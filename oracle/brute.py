@@ -23,13 +23,24 @@ def select_full_sort(row, K):
     return sorted(order[:K])
 
 
-def moc_forward_loops(X, W_gate, W_up, W_down, K):
-    """X[s][d], W_gate[d][F], W_up[d][F], W_down[F][d] as nested lists -> (D, sets)."""
+def select_grouped_full_sort(row, a, b):
+    """MoC_{a:b}: the a largest of every b consecutive channels, decided like select_full_sort."""
+    chosen = []
+    for first in range(0, len(row), b):
+        members = list(range(first, first + b))
+        members.sort(key=lambda j: (-_f32(row[j]), j))
+        chosen.extend(members[:a])
+    return sorted(chosen)
+
+
+def moc_forward_loops(X, W_gate, W_up, W_down, K, group=None):
+    """X[s][d], W_gate[d][F], W_up[d][F], W_down[F][d] as nested lists -> (D, sets).
+    group = (a, b) switches to the grouped selection of MoC_{a:b} (K is then ignored)."""
     s, d, F = len(X), len(X[0]), len(W_gate[0])
     D, sets = [], []
     for i in range(s):
         g = [sum(X[i][k] * W_gate[k][j] for k in range(d)) for j in range(F)]
-        C = select_full_sort(g, K)
+        C = select_full_sort(g, K) if group is None else select_grouped_full_sort(g, group[0], group[1])
         out = [0.0] * d
         for j in C:
             u = sum(X[i][k] * W_up[k][j] for k in range(d))

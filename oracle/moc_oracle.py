@@ -12,6 +12,10 @@ What each function follows:
   swiglu_forward/backward  Section "Activation memory profiling", Eqs. (FFN-1), (FFN-2).
   topk_mask                Section "Mixture-of-Channels architecture": M = TopK(G), row-wise,
                            largest signed values, exactly K ones per row.
+  grouped_topk_mask        The grouped Top-K of MoC_{a:b} (item "MoC with structured 2:8 sparsity" and
+                           the definition before Theorem 1): a entries are kept in every contiguous
+                           group of b entries of a row; b divides d_ffn.
+  moc_forward_grouped, moc_decode_grouped   the same layer and recipe with that mask.
   moc_forward*             Eqs. (MoC-1), (MoC-2).
   moc_backward             Section "Activation-efficient pre-training", Eqs. (bp-1)...(bp-5),
                            with S' and Z' recomputed from the stored G.M and U.M (MoC + GCP).
@@ -28,7 +32,9 @@ Pins (tests/test_oracle_*.py): a hand-worked example from Eq. (3) and (MoC-2), b
 full-sort selection, numpy/torch library selection routines, dense SwiGLU through torch's own
 silu at K = d_ffn, torch.autograd and central finite differences for the backward, torch's
 rms_norm, and the invariants (unselected channels contribute nothing, token independence,
-channel-permutation equivariance, decode == training forward).  No function here is unpinned.
+channel-permutation equivariance, decode == training forward); for the grouped mask: a hand example,
+the loop twin, b = d_ffn reducing to topk_mask, a = b reducing to dense SwiGLU, torch.topk on the
+reshaped row, exactly a per group, the 2:4 compatibility of 2:8 masks.  No function here is unpinned.
 """
 import numpy as np
 
@@ -97,6 +103,28 @@ def topk_mask(G, K, select_dtype=np.float32):
     return M
 
 
+def grouped_topk_mask(G, a, b, select_dtype=np.float32):
+    """Mask of MoC_{a:b}: in every contiguous group of b channels (channels q*b ... q*b + b - 1) the
+    a largest signed entries are marked, so each row holds a * d_ffn / b ones.  Same precision and
+    tie rule as topk_mask (float32 decision, lower channel first among equal values)."""
+    G = np.asarray(G)
+    s, F = G.shape
+    if b < 1 or F % b != 0:
+        raise ValueError("b must divide d_ffn")
+    if not (1 <= a <= b):
+        raise ValueError("a must satisfy 1 <= a <= b")
+    if not np.all(np.isfinite(G)):
+        raise ValueError("non-finite gate values")
+    key = G.astype(select_dtype)
+    M = np.zeros((s, F), dtype=bool)
+    for i in range(s):
+        for q in range(F // b):
+            group = key[i, q * b:(q + 1) * b]
+            order = np.argsort(-group, kind="stable")
+            M[i, q * b + order[:a]] = True
+    return M
+
+
 # ------------------------------------------------------------- Eqs. (MoC-1), (MoC-2)
 def moc_forward_given_mask(X, W_gate, W_up, W_down, M):
     X, W_gate, W_up, W_down = map(_f64, (X, W_gate, W_up, W_down))
@@ -112,6 +140,14 @@ def moc_forward_given_mask(X, W_gate, W_up, W_down, M):
 def moc_forward(X, W_gate, W_up, W_down, K):
     G = _f64(X) @ _f64(W_gate)
     M = topk_mask(G, K)
+    D, G, U = moc_forward_given_mask(X, W_gate, W_up, W_down, M)
+    return D, M, G, U
+
+
+def moc_forward_grouped(X, W_gate, W_up, W_down, a, b):
+    """MoC_{a:b}: Eqs. (MoC-1), (MoC-2) with the grouped mask in place of the row-wide Top-K."""
+    G = _f64(X) @ _f64(W_gate)
+    M = grouped_topk_mask(G, a, b)
     D, G, U = moc_forward_given_mask(X, W_gate, W_up, W_down, M)
     return D, M, G, U
 
@@ -197,6 +233,28 @@ def moc_decode(x, W_gate, W_up, W_down, K):
             acc += zj * W_down[j]
         out[b] = acc
         sets[b] = C
+    return (out[0], sets[0]) if single else (out, sets)
+
+
+def moc_decode_grouped(x, W_gate, W_up, W_down, a, b):
+    """The per-token recipe of moc_decode with the set C chosen group by group (MoC_{a:b})."""
+    x = _f64(x)
+    single = x.ndim == 1
+    xs = x[None, :] if single else x
+    W_gate, W_up, W_down = map(_f64, (W_gate, W_up, W_down))
+    B, d = xs.shape
+    K = W_gate.shape[1] // b * a
+    out = np.zeros((B, d), dtype=F64)
+    sets = np.empty((B, K), dtype=np.int32)
+    for t in range(B):
+        g = xs[t] @ W_gate
+        C = np.flatnonzero(grouped_topk_mask(g[None, :], a, b)[0])
+        acc = np.zeros(d, dtype=F64)
+        for j in C:
+            u_j = xs[t] @ W_up[:, j]
+            acc += silu(g[j]) * u_j * W_down[j]
+        out[t] = acc
+        sets[t] = C
     return (out[0], sets[0]) if single else (out, sets)
 
 

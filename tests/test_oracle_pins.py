@@ -271,3 +271,91 @@ def test_rmsnorm_against_torch_and_stack():
         Dd, _ = O.moc_decode(xn, Wg, Wu, Wd, 5)
         h_ref = h_ref + Dd
     np.testing.assert_allclose(h, h_ref, rtol=1e-11, atol=1e-13)
+
+
+# ----------------------------------------------------------- grouped Top-K (MoC_{a:b})
+GOLDEN_GROUPED = os.path.join(os.path.dirname(__file__), "golden", "grouped_example.json")
+
+
+def test_grouped_hand_example():
+    g = json.load(open(GOLDEN_GROUPED))
+    X, Wg, Wu, Wd = (np.array(g[k]) for k in ("X", "W_gate", "W_up", "W_down"))
+    D, M, G, U = O.moc_forward_grouped(X, Wg, Wu, Wd, g["a"], g["b"])
+    np.testing.assert_allclose(G, g["G"], rtol=0, atol=1e-15)
+    assert [list(np.flatnonzero(r)) for r in M] == g["C"]
+    np.testing.assert_allclose(D, g["D"], rtol=1e-14)
+    # the row-wide Top-2 of the same gate is a different set
+    assert [list(np.flatnonzero(r)) for r in O.topk_mask(G, 2)] == g["C_rowwide_top2"]
+    dvec, C = O.moc_decode_grouped(X[0], Wg, Wu, Wd, g["a"], g["b"])
+    np.testing.assert_allclose(dvec, g["D"][0], rtol=1e-14)
+    assert C.tolist() == g["C"][0]
+
+
+def test_grouped_mask_explicit_cases():
+    # ties inside a group go to the lower channel; -0.0 equals +0.0; negative groups still give a
+    row = np.array([[0.2, 0.2, -5.0, 0.2, -1.0, -3.0, -2.0, -4.0, 0.0, -0.0, -0.0, 0.0]])
+    M = O.grouped_topk_mask(row, 2, 4)
+    assert list(np.flatnonzero(M[0])) == [0, 1, 4, 6, 8, 9]
+    M = O.grouped_topk_mask(row, 1, 4)
+    assert list(np.flatnonzero(M[0])) == [0, 4, 8]
+    M = O.grouped_topk_mask(row, 3, 4)
+    assert list(np.flatnonzero(M[0])) == [0, 1, 3, 4, 5, 6, 8, 9, 10]
+    with pytest.raises(ValueError):
+        O.grouped_topk_mask(row, 2, 8)      # 8 does not divide 12
+    with pytest.raises(ValueError):
+        O.grouped_topk_mask(row, 5, 4)
+
+
+def test_grouped_mask_properties_and_library_routines():
+    rng = np.random.default_rng(77)
+    G = rng.standard_normal((37, 96)).astype(np.float32)
+    G[:, 5] = G[:, 3]                                    # planted ties inside a group
+    for a, b in ((2, 8), (1, 8), (2, 4), (3, 16), (1, 2), (4, 4)):
+        M = O.grouped_topk_mask(G, a, b)
+        Mg = M.reshape(37, 96 // b, b)
+        assert np.all(Mg.sum(axis=2) == a)
+        Gg = G.reshape(37, 96 // b, b).astype(np.float64)
+        if a < b:
+            lo_sel = np.where(Mg, Gg, np.inf).min(axis=2)
+            hi_unsel = np.where(~Mg, Gg, -np.inf).max(axis=2)
+            assert np.all(lo_sel >= hi_unsel)
+        # torch.topk on the reshaped row: same multiset of kept values in every group
+        tv = torch.topk(torch.from_numpy(G).reshape(37, 96 // b, b), a, dim=2).values.numpy()
+        kept = np.sort(np.where(Mg, Gg, -np.inf), axis=2)[:, :, b - a:]
+        np.testing.assert_array_equal(np.sort(tv, axis=2), kept.astype(np.float32))
+        # loop twin
+        for i in (0, 17, 36):
+            assert brute.select_grouped_full_sort([float(v) for v in G[i]], a, b) == list(np.flatnonzero(M[i]))
+    # one group spanning the whole row is the row-wide Top-K
+    np.testing.assert_array_equal(O.grouped_topk_mask(G, 11, 96), O.topk_mask(G, 11))
+    # any 2:8 mask has at most two ones in every aligned group of four (the 2:4 pattern of the
+    # structured-sparse matrix instructions)
+    M28 = O.grouped_topk_mask(G, 2, 8)
+    assert M28.reshape(37, 24, 4).sum(axis=2).max() <= 2
+
+
+def test_grouped_forward_reductions_and_twin():
+    X, Wg, Wu, Wd = _rand_layer(5, 6, 5, 16)
+    # a = b keeps every channel: dense SwiGLU
+    D_all, M_all, _, _ = O.moc_forward_grouped(X, Wg, Wu, Wd, 4, 4)
+    assert M_all.all()
+    np.testing.assert_allclose(D_all, O.swiglu_forward(X, Wg, Wu, Wd)[0], rtol=1e-13)
+    # b = d_ffn is the row-wide layer
+    D_row, M_row, _, _ = O.moc_forward(X, Wg, Wu, Wd, 5)
+    D_g, M_g, _, _ = O.moc_forward_grouped(X, Wg, Wu, Wd, 5, 16)
+    np.testing.assert_array_equal(M_row, M_g)
+    np.testing.assert_array_equal(D_row, D_g)
+    # loop twin and decode recipe on 2:8
+    D28, M28, _, _ = O.moc_forward_grouped(X, Wg, Wu, Wd, 2, 8)
+    D_loops, sets = brute.moc_forward_loops(X.tolist(), Wg.tolist(), Wu.tolist(), Wd.tolist(), None, group=(2, 8))
+    assert sets == [list(np.flatnonzero(r)) for r in M28]
+    np.testing.assert_allclose(D28, np.array(D_loops), rtol=1e-12, atol=1e-14)
+    D_dec, C_dec = O.moc_decode_grouped(X, Wg, Wu, Wd, 2, 8)
+    np.testing.assert_allclose(D_dec, D28, rtol=1e-12, atol=1e-14)
+    assert C_dec.tolist() == sets
+    # unselected channels contribute nothing
+    Wu2, Wd2 = Wu.copy(), Wd.copy()
+    never = ~M28.any(axis=0)
+    Wu2[:, never] = 1e6
+    Wd2[never, :] = -1e6
+    np.testing.assert_array_equal(O.moc_forward_given_mask(X, Wg, Wu2, Wd2, M28)[0], D28)
