@@ -105,6 +105,26 @@ moc_status moc_swiglu_bwd(const moc_shape* shape, const void* x, const void* wg,
 moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_t ldg,
                          int32_t* idx, float* gsel, void* hip_stream);
 
+/* MoC_{a:b}, the grouped Top-K variant (item "MoC with structured 2:8 sparsity" of section
+ * "Mixture-of-Channels architecture"; a:b defined before Theorem 1): the mask keeps the a largest
+ * signed gate values of every contiguous group of b channels (channels q*b .. q*b+b-1), ties to
+ * the lower channel.  b must be 4, 8 or 16 and divide F, 1 <= a <= b, and shape->K must equal
+ * a*F/b; otherwise MOC_ERR_BAD_ARG.  Arguments, layouts, workspace (moc_workspace_bytes with
+ * MOC_OP_FWD / MOC_OP_DECODE and the same shape) and ownership are those of moc_ffn_fwd /
+ * moc_ffn_decode / moc_topk_rows; idx rows ascend, slot q*a + r holds the r-th kept channel of
+ * group q.  The stored set feeds moc_ffn_bwd unchanged. */
+moc_status moc_ffn_fwd_grouped(const moc_shape* shape, int32_t a, int32_t b, const void* x,
+                               const void* wg, const void* wu, const void* wd, void* y,
+                               int32_t* idx, void* gvals, void* uvals,
+                               void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_ffn_decode_grouped(const moc_shape* shape, int32_t a, int32_t b, const void* x,
+                                  const void* wg, const void* wu, const void* wd, void* y,
+                                  int32_t* idx_or_null, void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_topk_grouped_rows(int32_t T, int32_t F, int32_t a, int32_t b, const float* g,
+                                 int64_t ldg, int32_t* idx, float* gsel, void* hip_stream);
+
 /* RMSNorm of each row, y = x / sqrt(mean(x^2) + eps) . gain (section "Activation memory
  * profiling", RMSNorm item); h, out are [T,d] in dtype, gain is [d] in dtype. */
 moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain,

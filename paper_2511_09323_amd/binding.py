@@ -18,7 +18,7 @@ OP_FWD, OP_BWD, OP_DECODE, OP_SWIGLU_FWD, OP_SWIGLU_BWD = range(5)
 
 EXPORTS = (
     "moc_workspace_bytes", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
-    "moc_swiglu_bwd", "moc_topk_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
+    "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
     "moc_timing_collect", "moc_timing_get", "moc_timing_reset", "moc_status_string",
     "moc_last_error", "moc_version",
 )
@@ -62,6 +62,12 @@ def load_library():
     lib.moc_swiglu_bwd.argtypes = [shp] + [vp] * 12 + [sz, vp]
     lib.moc_topk_rows.restype = ctypes.c_int
     lib.moc_topk_rows.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp]
+    lib.moc_ffn_fwd_grouped.restype = ctypes.c_int
+    lib.moc_ffn_fwd_grouped.argtypes = [shp, i32, i32] + [vp] * 9 + [sz, vp]
+    lib.moc_ffn_decode_grouped.restype = ctypes.c_int
+    lib.moc_ffn_decode_grouped.argtypes = [shp, i32, i32] + [vp] * 7 + [sz, vp]
+    lib.moc_topk_grouped_rows.restype = ctypes.c_int
+    lib.moc_topk_grouped_rows.argtypes = [i32, i32, i32, i32, vp, i64, vp, vp, vp]
     lib.moc_rmsnorm.restype = ctypes.c_int
     lib.moc_rmsnorm.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, vp, vp]
     lib.moc_residual_add.restype = ctypes.c_int
@@ -264,6 +270,73 @@ def moc_topk_rows(g, K):
     idx = torch.empty((T, K), dtype=torch.int32, device=g.device)
     gsel = torch.empty((T, K), dtype=torch.float32, device=g.device)
     _check(lib.moc_topk_rows(T, F, K, ctypes.c_void_p(g.data_ptr()), ldg, _ptr(idx), _ptr(gsel), _stream()))
+    return idx, gsel
+
+
+def _grouped_K(F, a, b):
+    return F // b * a if b > 0 and F % b == 0 else max(1, min(F, a))   # the library reports bad a:b itself
+
+
+def moc_ffn_fwd_grouped(x, wg, wu, wd, a, b, ws=None, out=None):
+    """MoC_{a:b} forward (a kept of every b consecutive channels).  Returns (y, idx, gvals, uvals)
+    with K = a*F/b columns, usable by moc_ffn_bwd as they are."""
+    lib = load_library()
+    T, d = x.shape
+    F = wg.shape[0]
+    K = _grouped_K(F, a, b)
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((T, d), dtype=dt, device=x.device)
+        idx = torch.empty((T, K), dtype=torch.int32, device=x.device)
+        gvals = torch.empty((T, K), dtype=dt, device=x.device)
+        uvals = torch.empty((T, K), dtype=dt, device=x.device)
+    else:
+        y, idx, gvals, uvals = out
+    ws, ws_bytes = _workspace(ws, T, d, F, K, dt, OP_FWD, x.device)
+    shp = _shape(T, d, F, K, code)
+    _check(lib.moc_ffn_fwd_grouped(ctypes.byref(shp), a, b, _ptr(x, dt, (T, d), "x"), _ptr(wg, dt, (F, d), "wg"),
+                                   _ptr(wu, dt, (F, d), "wu"), _ptr(wd, dt, (F, d), "wd"), _ptr(y, dt, (T, d), "y"),
+                                   _ptr(idx, torch.int32, (T, K), "idx"), _ptr(gvals, dt, (T, K), "gvals"),
+                                   _ptr(uvals, dt, (T, K), "uvals"), _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return y, idx, gvals, uvals
+
+
+def moc_ffn_decode_grouped(x, wg, wu, wd, a, b, ws=None, want_idx=True, out=None):
+    """MoC_{a:b} decode for a batch x [B,d], B <= 16.  Returns (y, idx or None)."""
+    lib = load_library()
+    B, d = x.shape
+    F = wg.shape[0]
+    K = _grouped_K(F, a, b)
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((B, d), dtype=dt, device=x.device)
+        idx = torch.empty((B, K), dtype=torch.int32, device=x.device) if want_idx else None
+    else:
+        y, idx = out
+    ws, ws_bytes = _workspace(ws, B, d, F, K, dt, OP_DECODE, x.device)
+    shp = _shape(B, d, F, K, code)
+    _check(lib.moc_ffn_decode_grouped(ctypes.byref(shp), a, b, _ptr(x, dt, (B, d), "x"), _ptr(wg, dt, (F, d), "wg"),
+                                      _ptr(wu, dt, (F, d), "wu"), _ptr(wd, dt, (F, d), "wd"),
+                                      _ptr(y, dt, (B, d), "y"),
+                                      _ptr(idx, torch.int32, (B, K), "idx") if idx is not None else None,
+                                      _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return y, idx
+
+
+def moc_topk_grouped_rows(g, a, b):
+    """Grouped Top-K (a of every b consecutive columns) of an fp32 matrix g [T,F] (rows may be
+    strided).  Returns (idx [T, a*F/b] ascending, gsel)."""
+    lib = load_library()
+    T, F = g.shape
+    if not g.is_cuda or g.dtype != torch.float32 or g.stride(1) != 1:
+        raise MocError("MOC_ERR_BAD_ARG", "g must be a GPU fp32 matrix with unit column stride")
+    ldg = g.stride(0) if T > 1 else F
+    K = _grouped_K(F, a, b)
+    idx = torch.empty((T, K), dtype=torch.int32, device=g.device)
+    gsel = torch.empty((T, K), dtype=torch.float32, device=g.device)
+    _check(lib.moc_topk_grouped_rows(T, F, a, b, ctypes.c_void_p(g.data_ptr()), ldg, _ptr(idx), _ptr(gsel), _stream()))
     return idx, gsel
 
 

@@ -6,6 +6,7 @@
 // keep x in LDS.  All are bandwidth-bound; the arithmetic is fp32 FMA on the vector ALU.
 #pragma once
 #include "common.h"
+#include "group_select.h"
 
 namespace moc {
 
@@ -89,6 +90,91 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
     }
 }
 
+// Grouped selection of MoC_{a:b} for one group and one token: vals[i * stride] are the gate values of
+// channels c0 .. c0 + GB - 1; the kept channels go to slots q*ga .. q*ga + ga - 1 of the token's row.
+template <int GB>
+__device__ __forceinline__ void decode_group_select(const float* vals, int stride, int c0, int q, int ga,
+                                                    int32_t* idx_row, float* gsel_row) {
+    float v[GB];
+#pragma unroll
+    for (int i = 0; i < GB; ++i) v[i] = vals[i * stride];
+    int rank[GB];
+    group_ranks<GB>(v, rank);
+    int r = 0;
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+        if (rank[i] < ga && r < ga) {                  // r < ga only matters for non-finite input
+            idx_row[q * ga + r] = c0 + i;
+            gsel_row[q * ga + r] = v[i];
+            ++r;
+        }
+    }
+}
+
+// Gate projection fused with the grouped selection of MoC_{a:b}: a workgroup owns one group of GB
+// consecutive channels at a time (wave w computes rows w, w + 4, ... of the group), the GB x B gate
+// values meet in LDS and thread b selects for token b.  No gate row is written to memory.
+template <class E, int BT, int GB>
+__global__ __launch_bounds__(256) void decode_gate_group_kernel(const E* __restrict__ x, const E* __restrict__ wg,
+                                                                int B, int d, int F, int ga, int K,
+                                                                int32_t* __restrict__ idx, float* __restrict__ gsel) {
+    constexpr int CN = Chunk<E>::N;
+    extern __shared__ __align__(16) unsigned char dec_smem[];
+    E* xs = reinterpret_cast<E*>(dec_smem);
+    __shared__ float gl[2][GB][BT];
+    for (int i = threadIdx.x * CN; i < BT * d; i += 256 * CN) {
+        int b = i / d;
+        u32x4_t v = {0, 0, 0, 0};
+        if (b < B) v = *reinterpret_cast<const u32x4_t*>(x + i);
+        *reinterpret_cast<u32x4_t*>(xs + i) = v;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int UN = 8;      // 16-byte chunks of the row in flight per lane
+    int it = 0;
+    for (int q = blockIdx.x; q < F / GB; q += gridDim.x, ++it) {
+        for (int rr = wave; rr < GB; rr += 4) {
+            const E* wrow = wg + (int64_t)(q * GB + rr) * d;
+            float acc[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+            for (int k0 = lane * CN; k0 < d; k0 += 64 * CN * UN) {
+                u32x4_t raw[UN];
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int k = k0 + u * 64 * CN;
+                    raw[u] = u32x4_t{0, 0, 0, 0};
+                    if (k < d) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + k));
+                }
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int k = k0 + u * 64 * CN;
+                    if (k < d) {
+                        float w[CN];
+                        Chunk<E>::unpack(raw[u], w);
+#pragma unroll
+                        for (int b = 0; b < BT; ++b) {
+                            float xv[CN];
+                            Chunk<E>::load(xs + b * d + k, xv);
+#pragma unroll
+                            for (int e = 0; e < CN; ++e) acc[b] = fmaf(w[e], xv[e], acc[b]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float s = wave_sum(acc[b]);
+                if (lane == 0) gl[it & 1][rr][b] = s;
+            }
+        }
+        __syncthreads();       // gl[it & 1] complete; gl[(it + 1) & 1] is free again (read two barriers ago)
+        if (threadIdx.x < B)
+            decode_group_select<GB>(&gl[it & 1][0][threadIdx.x], BT, q * GB, q, ga, idx + (int64_t)threadIdx.x * K,
+                                    gsel + (int64_t)threadIdx.x * K);
+    }
+}
+
 // Gate projection for batches of 5..16 tokens on the matrix cores (bf16 only):
 //   g[b, j] = x[b] . wg[j]  as D[row j][token b] tiles of v_mfma_f32_16x16x32_bf16.
 // A 768-thread workgroup owns 48 consecutive channel rows (230 workgroups for 11008 rows, one per
@@ -97,10 +183,14 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
 // a 128-byte line); x[16, d] sits in LDS (rows padded by 16 bytes) and supplies the second MFMA
 // input with the same k assignment.  The four partial tiles of a row group are summed through LDS.
 // Needs d % 1024 == 0 (every wave's share is a whole number of 4-step prefetch groups).
+// GB = 0 writes the gate rows g[B, ldg]; GB = 4, 8, 16 selects the a largest of every GB channels
+// instead (MoC_{a:b}; 48 rows are a whole number of groups) and writes idx / gsel [B, K] only.
 typedef __bf16 dec_bf16x8_t __attribute__((ext_vector_type(8)));
+template <int GB>
 __global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __restrict__ x,
                                                                 const bf16_t* __restrict__ wg, int B, int d, int F,
-                                                                float* __restrict__ g, int64_t ldg) {
+                                                                float* __restrict__ g, int64_t ldg, int ga, int K,
+                                                                int32_t* __restrict__ idx, float* __restrict__ gsel) {
     extern __shared__ __align__(16) unsigned char dec_smem[];
     const int xpitch = d * 2 + 16;                                   // bytes per staged token row
     float* red = reinterpret_cast<float*>(dec_smem + 16 * xpitch);   // [3 row groups][4 quarters][256]
@@ -156,14 +246,30 @@ __global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __r
 #pragma unroll
         for (int o = 1; o < 4; ++o) s += *reinterpret_cast<const f32x4_t*>(red + ((rg * 4 + o) * 64 + lane) * 4);
         const int b = lane & 15, r = row0 + 4 * (lane >> 4);
-        if (b < B) {
-            if (r + 3 < F) *reinterpret_cast<f32x4_t*>(g + (int64_t)b * ldg + r) = s;
-            else {
+        if (GB == 0) {
+            if (b < B) {
+                if (r + 3 < F) *reinterpret_cast<f32x4_t*>(g + (int64_t)b * ldg + r) = s;
+                else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (r + e < F) g[(int64_t)b * ldg + r + e] = s[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (r + e < F) g[(int64_t)b * ldg + r + e] = s[e];
+                }
             }
+        } else {
+            float* tile = red + 3 * 4 * 256;                       // [48 rows][17]
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tile[(rg * 16 + 4 * (lane >> 4) + e) * 17 + b] = s[e];
         }
+    }
+    if (GB != 0) {
+        __syncthreads();
+        constexpr int GBS = GB == 0 ? 8 : GB;
+        const float* tile = red + 3 * 4 * 256;
+        const int grp = tid >> 4, b = tid & 15;                     // group of this workgroup's 48 rows, token
+        const int c0 = blockIdx.x * 48 + grp * GBS;
+        if (grp < 48 / GBS && b < B && c0 < F)
+            decode_group_select<GBS>(tile + grp * GBS * 17 + b, 17, c0, c0 / GBS, ga, idx + (int64_t)b * K,
+                                     gsel + (int64_t)b * K);
     }
 }
 

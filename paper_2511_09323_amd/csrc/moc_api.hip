@@ -14,6 +14,7 @@
 #include "../../include/moc.h"
 #include "common.h"
 #include "decode_kernels.h"
+#include "group_select.h"
 #include "epilogue.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
@@ -239,6 +240,29 @@ moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t s
     return run_topk_lds<E, NT, 1, FUSED>(name, a, T, st);
 }
 
+// Grouped Top-K of MoC_{a:b}: one thread per group of gb channels.
+moc_status check_group(int F, int K, int ga, int gb) {
+    if (gb != 4 && gb != 8 && gb != 16) return fail(MOC_ERR_BAD_ARG, "group size b must be 4, 8 or 16 (got %d)", gb);
+    if (ga < 1 || ga > gb) return fail(MOC_ERR_BAD_ARG, "a must satisfy 1 <= a <= b (got a=%d, b=%d)", ga, gb);
+    if (F % gb != 0) return fail(MOC_ERR_BAD_ARG, "b = %d must divide F = %d", gb, F);
+    if (K != F / gb * ga) return fail(MOC_ERR_BAD_ARG, "K = %d must equal a*F/b = %d", K, F / gb * ga);
+    return MOC_OK;
+}
+
+template <class E, bool FUSED>
+moc_status run_group_select(const char* name, const TopkArgs<E>& a, int T, int ga, int gb, hipStream_t st) {
+    const int vec_ok = a.ldg % 4 == 0 && aligned16(a.g);
+    if (FUSED && (!vec_ok || a.ldz % 64 != 0 || a.ldu % 64 != 0)) return fail(MOC_ERR_BAD_ARG, "%s: unaligned workspace", name);
+    const int64_t groups = (int64_t)T * ((FUSED ? a.ldz : (int64_t)a.F) / gb);
+    const unsigned grid = (unsigned)((groups + 255) / 256);
+    Span span(name, st);
+    if (gb == 4) hipLaunchKernelGGL((group_select_kernel<E, 4, FUSED>), dim3(grid), dim3(256), 0, st, a, T, ga, vec_ok);
+    else if (gb == 8) hipLaunchKernelGGL((group_select_kernel<E, 8, FUSED>), dim3(grid), dim3(256), 0, st, a, T, ga, vec_ok);
+    else hipLaunchKernelGGL((group_select_kernel<E, 16, FUSED>), dim3(grid), dim3(256), 0, st, a, T, ga, vec_ok);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
 // ------------------------------------------------------------------- workspace layouts
 struct Dims {
     int T, d, F, K;
@@ -323,7 +347,7 @@ moc_status down_projection(const Dims& D, const E* Zd, const E* wd, E* y, hipStr
 // ----------------------------------------------------------------------------- forward
 template <class E>
 moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx, E* gvals,
-                    E* uvals, void* ws, hipStream_t st) {
+                    E* uvals, void* ws, hipStream_t st, int ga = 0, int gb = 0) {
     FwdWs<E> W(ws, D, false);
     moc_status s;
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
@@ -334,7 +358,9 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     if ((s = run_gemm<E, false, false>("gemm_up", pu, EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
-    if ((s = run_topk<E, 256, true>("topk_select_act", a, D.T, st)) != MOC_OK) return s;
+    if (gb == 0) s = run_topk<E, 256, true>("topk_select_act", a, D.T, st);
+    else s = run_group_select<E, true>("group_select_act", a, D.T, ga, gb, st);      // MoC_{a:b}
+    if (s != MOC_OK) return s;
     return down_projection<E>(D, W.Zd, wd, y, st);
 }
 
@@ -420,38 +446,84 @@ moc_status decode_gate(const Dims& D, const E* x, const E* wg, float* g, hipStre
     return MOC_OK;
 }
 
+// Gate projection fused with the grouped selection (MoC_{a:b}) on the vector ALU.
+template <class E, int BT, int GB>
+moc_status decode_gate_group(const Dims& D, const E* x, const E* wg, int ga, int32_t* idx, float* gsel, hipStream_t st) {
+    const size_t lds = (size_t)BT * D.d * sizeof(E);
+    if (lds > 156 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large for LDS staging", D.d);
+    auto kern = decode_gate_group_kernel<E, BT, GB>;
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    156 * 1024));
+        attr = true;
+    }
+    Span span("decode_gate_select", st);
+    const int per_cu = lds > 76 * 1024 ? 1 : (lds > 36 * 1024 ? 2 : (lds > 16 * 1024 ? 4 : 8));
+    const int grid = std::min(D.F / GB, 256 * per_cu);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, x, wg, D.T, D.d, D.F, ga, D.K, idx, gsel);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E, int BT>
+moc_status decode_gate_group_b(const Dims& D, const E* x, const E* wg, int ga, int gb, int32_t* idx, float* gsel,
+                               hipStream_t st) {
+    if (gb == 4) return decode_gate_group<E, BT, 4>(D, x, wg, ga, idx, gsel, st);
+    if (gb == 8) return decode_gate_group<E, BT, 8>(D, x, wg, ga, idx, gsel, st);
+    return decode_gate_group<E, BT, 16>(D, x, wg, ga, idx, gsel, st);
+}
+
+template <int GB>
+moc_status launch_decode_gate_mfma(const Dims& D, const bf16_t* x, const bf16_t* wg, float* g, int ga, int32_t* idx,
+                                   float* gsel, size_t lds, hipStream_t st) {
+    auto kern = decode_gate_mfma_kernel<GB>;
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - 64));
+        attr = true;
+    }
+    Span span(GB == 0 ? "decode_gate" : "decode_gate_select", st);
+    hipLaunchKernelGGL(kern, dim3((D.F + 47) / 48), dim3(768), lds, st, x, wg, D.T, D.d, D.F, g, (int64_t)D.ldF, ga, D.K,
+                       idx, gsel);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+// ga:gb = 0:0 is the row-wide Top-K; otherwise the grouped selection of MoC_{a:b}, which is decided
+// inside the gate kernel (a group's channels meet in one workgroup) and needs no selection launch.
 template <class E>
 moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx_out,
-                       void* ws, hipStream_t st) {
+                       void* ws, hipStream_t st, int ga = 0, int gb = 0) {
     DecodeWs W(ws, D);
     const int B = D.T;
     int32_t* idx = idx_out ? idx_out : W.idx;
     moc_status s;
-    if (B == 1) s = decode_gate<E, 1>(D, x, wg, W.g, st);
-    else if (B <= 4) s = decode_gate<E, 4>(D, x, wg, W.g, st);
-    else {
-        const size_t mfma_lds = (size_t)16 * (D.d * 2 + 16) + 4 * 4 * 256 * sizeof(float);
-        if (std::is_same<E, bf16_t>::value && D.d % 1024 == 0 && mfma_lds <= 160 * 1024 - 64 &&
-            !options().force_generic) {
-            static bool attr = false;
-            if (!attr) {
-                HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_gate_mfma_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64));
-                attr = true;
-            }
-            Span span("decode_gate", st);
-            hipLaunchKernelGGL(decode_gate_mfma_kernel, dim3((D.F + 47) / 48), dim3(768), mfma_lds, st,
-                               reinterpret_cast<const bf16_t*>(x), reinterpret_cast<const bf16_t*>(wg), B, D.d, D.F, W.g,
-                               (int64_t)D.ldF);
-            HIP_TRY(hipGetLastError());
-            s = MOC_OK;
-        } else {
-            s = decode_gate<E, 16>(D, x, wg, W.g, st);
-        }
+    const size_t mfma_lds = (size_t)16 * (D.d * 2 + 16) + 4 * 4 * 256 * sizeof(float);
+    const bool mfma_gate = B > 4 && std::is_same<E, bf16_t>::value && D.d % 1024 == 0 && mfma_lds <= 160 * 1024 - 64 &&
+                           !options().force_generic;
+    if (mfma_gate) {
+        const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
+        const bf16_t* wb = reinterpret_cast<const bf16_t*>(wg);
+        if (gb == 0) s = launch_decode_gate_mfma<0>(D, xb, wb, W.g, 0, idx, W.gsel, mfma_lds, st);
+        else if (gb == 4) s = launch_decode_gate_mfma<4>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
+        else if (gb == 8) s = launch_decode_gate_mfma<8>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
+        else s = launch_decode_gate_mfma<16>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
+    } else if (gb == 0) {
+        if (B == 1) s = decode_gate<E, 1>(D, x, wg, W.g, st);
+        else if (B <= 4) s = decode_gate<E, 4>(D, x, wg, W.g, st);
+        else s = decode_gate<E, 16>(D, x, wg, W.g, st);
+    } else {
+        if (B == 1) s = decode_gate_group_b<E, 1>(D, x, wg, ga, gb, idx, W.gsel, st);
+        else if (B <= 4) s = decode_gate_group_b<E, 4>(D, x, wg, ga, gb, idx, W.gsel, st);
+        else s = decode_gate_group_b<E, 16>(D, x, wg, ga, gb, idx, W.gsel, st);
     }
     if (s != MOC_OK) return s;
-    TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
-    if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
+    if (gb == 0) {
+        TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+        if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
+    }
     const int P = decode_splits(B, D.K);
     constexpr int NIT = 8;
     const size_t fused_lds = (size_t)D.d * sizeof(E) + (size_t)8 * D.d * sizeof(float);
@@ -611,6 +683,54 @@ moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     TopkArgs<float> a{g, ldg, F, K, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
     return run_topk<float, 256, false>("topk_rows", a, T, st);
+}
+
+moc_status moc_ffn_fwd_grouped(const moc_shape* shape, int32_t ga, int32_t gb, const void* x, const void* wg,
+                               const void* wu, const void* wd, void* y, int32_t* idx, void* gvals, void* uvals, void* ws,
+                               size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    if ((s = check_group(shape->F, shape->K, ga, gb)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_WS(MOC_OP_FWD);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return fwd_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd, (bf16_t*)y,
+                                idx, (bf16_t*)gvals, (bf16_t*)uvals, ws, st, ga, gb);
+    return fwd_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y, idx,
+                           (float*)gvals, (float*)uvals, ws, st, ga, gb);
+}
+
+moc_status moc_ffn_decode_grouped(const moc_shape* shape, int32_t ga, int32_t gb, const void* x, const void* wg,
+                                  const void* wu, const void* wd, void* y, int32_t* idx_or_null, void* ws,
+                                  size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, true);
+    if (s != MOC_OK) return s;
+    if ((s = check_group(shape->F, shape->K, ga, gb)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y);
+    if (idx_or_null && !aligned16(idx_or_null)) return fail(MOC_ERR_BAD_ARG, "idx is not 16-byte aligned");
+    CHECK_WS(MOC_OP_DECODE);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return decode_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                   (bf16_t*)y, idx_or_null, ws, st, ga, gb);
+    return decode_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y,
+                              idx_or_null, ws, st, ga, gb);
+}
+
+moc_status moc_topk_grouped_rows(int32_t T, int32_t F, int32_t ga, int32_t gb, const float* g, int64_t ldg, int32_t* idx,
+                                 float* gsel, void* hip_stream) {
+    if (T < 1 || F < 1) return fail(MOC_ERR_BAD_ARG, "need T >= 1 and F >= 1 (T=%d F=%d)", T, F);
+    if (gb < 1 || F % gb != 0) return fail(MOC_ERR_BAD_ARG, "b = %d must divide F = %d", gb, F);
+    moc_status s = check_group(F, F / gb * ga, ga, gb);
+    if (s != MOC_OK) return s;
+    if (ldg < F) return fail(MOC_ERR_BAD_ARG, "ldg < F");
+    CHECK_PTR(g); CHECK_PTR(idx); CHECK_PTR(gsel);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    TopkArgs<float> a{g, ldg, F, F / gb * ga, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+    return run_group_select<float, false>("group_select_rows", a, T, ga, gb, st);
 }
 
 moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain, float eps, void* out,

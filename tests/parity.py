@@ -85,3 +85,36 @@ def oracle_backward_for(L, idx, gvals, uvals):
     M, GM, UM = O.expand_saved(idx, gvals, uvals, F)
     dX, dWg, dWu, dWd = O.moc_backward(X, Wg, Wu, Wd, M, GM, UM, L["dy"].astype(np.float64))
     return dX, dWg.T, dWu.T, dWd
+
+
+def check_grouped_index_sets(idx_gpu, G64, a, b):
+    """The grouped counterpart of check_index_sets for MoC_{a:b}: every row ascends, every group of
+    b channels holds exactly a kept channels, and a group's kept set equals the oracle's unless the
+    group's a-th / (a+1)-th fp32 gate values are within the 1e-6 window, where any set that keeps
+    everything clearly above and nothing clearly below is accepted.  A group's threshold can lie
+    arbitrarily close to zero (the row-wide one never does), while the rounding error of an fp32
+    dot product scales with its terms, not with its possibly cancelling sum; the window is
+    therefore 1e-6 relative to the larger of |threshold| and the row's RMS gate value.  Returns
+    the rows in which some group needed the window."""
+    idx_gpu = np.asarray(idx_gpu)
+    T, F = G64.shape
+    K = F // b * a
+    assert idx_gpu.shape == (T, K)
+    assert np.all(idx_gpu >= 0) and np.all(idx_gpu < F)
+    if K > 1:
+        assert np.all(np.diff(idx_gpu, axis=1) > 0), "idx rows must ascend strictly"
+    M_gpu = O.mask_from_idx(idx_gpu, F)
+    assert np.all(M_gpu.reshape(T, F // b, b).sum(axis=2) == a), "every group must keep exactly a channels"
+    M_ref = O.grouped_topk_mask(G64, a, b)
+    differing = np.flatnonzero((M_ref != M_gpu).any(axis=1))
+    g32 = G64.astype(np.float32)
+    for t in differing:
+        rms = float(np.sqrt(np.mean(g32[t].astype(np.float64) ** 2)))
+        for q in np.flatnonzero((M_ref[t] != M_gpu[t]).reshape(F // b, b).any(axis=1)):
+            grp = g32[t, q * b:(q + 1) * b].astype(np.float64)
+            tau = np.sort(grp)[b - a]
+            tol = TIE_WINDOW * max(abs(tau), rms, 1e-30)
+            kept = M_gpu[t, q * b:(q + 1) * b]
+            assert np.all(kept[grp > tau + tol]), "row %d group %d drops a channel clearly above the threshold" % (t, q)
+            assert not np.any(kept[grp < tau - tol]), "row %d group %d keeps a channel clearly below it" % (t, q)
+    return differing

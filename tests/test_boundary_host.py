@@ -90,6 +90,19 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert rc == -3
     assert lib.moc_topk_rows(4, 16, 17, fake, 16, fake, fake, None) == -1
     assert lib.moc_topk_rows(4, 16, 4, fake, 8, fake, fake, None) == -1     # ldg < F
+    # grouped Top-K (MoC_{a:b}): b in {4, 8, 16} dividing F, 1 <= a <= b, K = a F / b
+    s = B.MocShape(4, 64, 128, 32, B.MOC_BF16)
+    for a, b in ((2, 8), ):
+        assert lib.moc_ffn_fwd_grouped(ctypes.byref(s), a, b, *([fake] * 9), 16, None) == -2     # valid a:b, short workspace
+    for a, b in ((2, 4), (0, 8), (9, 8), (2, 5), (2, 2)):
+        rc = lib.moc_ffn_fwd_grouped(ctypes.byref(s), a, b, *([fake] * 9), 1 << 30, None)
+        assert rc == -1, (a, b)
+        rc = lib.moc_ffn_decode_grouped(ctypes.byref(s), a, b, *([fake] * 7), 1 << 30, None)
+        assert rc == -1, (a, b)
+    s = B.MocShape(4, 64, 100, 50, B.MOC_BF16)           # 8 does not divide F
+    assert lib.moc_ffn_fwd_grouped(ctypes.byref(s), 4, 8, *([fake] * 9), 1 << 30, None) == -1
+    assert lib.moc_topk_grouped_rows(4, 20, 2, 8, fake, 20, fake, fake, None) == -1
+    assert lib.moc_topk_grouped_rows(4, 16, 2, 8, fake, 8, fake, fake, None) == -1      # ldg < F
     assert lib.moc_rmsnorm(0, 16, 0, fake, fake, 1e-5, fake, None) == -1
     assert lib.moc_residual_add(4, 16, 5, fake, fake, None) == -1
 

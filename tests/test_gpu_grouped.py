@@ -1,0 +1,159 @@
+"""GPU parity for MoC_{a:b}, the grouped Top-K variant (a channels kept of every b consecutive
+ones): selection alone, training forward + backward, and decode, through the C ABI against the
+CPU oracle.  Same rules as the row-wide tests: index sets bit-exact outside the 1e-6 near-tie
+window (applied per group), values within 1e-4 (fp32) / 2e-2 (bf16) max-norm relative error."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_09323_amd as moc
+from oracle import moc_oracle as O
+from paper_2511_09323_amd import inputs
+from paper_2511_09323_amd.configs import CONFIGS
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_layer(L, dtype):
+    return {k: P.to_dev(v, dtype) for k, v in L.items()}
+
+
+def _select_case(g_np, a, b):
+    g = torch.from_numpy(g_np).cuda()
+    idx, gsel = moc.moc_topk_grouped_rows(g, a, b)
+    torch.cuda.synchronize()
+    ref = np.stack([np.flatnonzero(r) for r in O.grouped_topk_mask(g_np, a, b)])
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref)
+    want = np.take_along_axis(g_np, ref, axis=1)
+    got = gsel.cpu().numpy()
+    assert np.array_equal(got == 0, want == 0)
+    np.testing.assert_array_equal(np.where(want == 0, 0.0, got), np.where(want == 0, 0.0, want))
+
+
+def test_grouped_select_bit_exact():
+    rng = np.random.default_rng(17)
+    for T, F, a, b in [(5, 8, 2, 8), (3, 16, 1, 4), (9, 336, 2, 8), (16, 1376, 2, 8), (8, 5464, 2, 8), (4, 11008, 2, 8),
+                       (4, 11008, 1, 8), (2, 32768, 3, 16), (3, 1024, 4, 4), (2, 2052, 3, 4), (300, 96, 5, 16)]:
+        say("[group] random T=%d F=%d %d:%d" % (T, F, a, b))
+        _select_case(rng.standard_normal((T, F)).astype(np.float32), a, b)
+    say("[group] ties, signed zeros, constant and negative rows")
+    g = np.zeros((6, 304), dtype=np.float32)
+    g[0] = 1.0
+    g[1] = np.tile(np.array([1, 2, 3, 1], dtype=np.float32), 76)
+    g[2] = -np.abs(rng.standard_normal(304)).astype(np.float32)
+    g[3, ::2] = -0.0
+    g[4] = np.round(rng.standard_normal(304) * 2).astype(np.float32)
+    g[5] = np.linspace(-1, 1, 304, dtype=np.float32)[::-1]
+    for a, b in ((1, 4), (2, 4), (2, 8), (7, 8), (1, 16), (9, 16), (16, 16)):
+        _select_case(g, a, b)
+    say("[group] strided input (ldg not a multiple of 4)")
+    base_np = rng.standard_normal((6, 1001)).astype(np.float32)
+    view = torch.from_numpy(base_np).cuda()[:, :992]
+    idx, _ = moc.moc_topk_grouped_rows(view, 2, 8)
+    torch.cuda.synchronize()
+    ref = np.stack([np.flatnonzero(r) for r in O.grouped_topk_mask(base_np[:, :992], 2, 8)])
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref)
+
+
+def test_grouped_bad_arguments_are_rejected():
+    g = torch.zeros((2, 20), dtype=torch.float32, device="cuda")
+    for a, b in ((2, 8), (0, 4), (5, 4), (1, 5), (1, 2)):
+        with pytest.raises(moc.MocError):
+            moc.moc_topk_grouped_rows(g, a, b)
+
+
+def run_grouped_fwd_bwd(tag, cfg_index, T, d, F, a, b, dtype, bwd=True):
+    K = F // b * a
+    say("[case] %s grouped %d:%d T=%d d=%d F=%d K=%d dtype=%s" % (tag, a, b, T, d, F, K, dtype))
+    tol = P.TOL[dtype]
+    L = inputs.make_layer(cfg_index, T, d, F, dtype, with_dy=True)
+    Gd = gpu_layer(L, dtype)
+    y, idx, gvals, uvals = moc.moc_ffn_fwd_grouped(Gd["x"], Gd["wg"], Gd["wu"], Gd["wd"], a, b)
+    torch.cuda.synchronize()
+    idx_np = idx.cpu().numpy()
+    D, gv_ref, uv_ref, G64 = P.oracle_forward_for(L, idx_np)
+    window = P.check_grouped_index_sets(idx_np, G64, a, b)
+    say("  idx sets: %d of %d rows with a group inside the near-tie window" % (len(window), T))
+    assert len(window) <= max(2, T // 100)
+    e = [P.assert_close("y", P.to_np(y), D, tol), P.assert_close("gvals", P.to_np(gvals), gv_ref, tol),
+         P.assert_close("uvals", P.to_np(uvals), uv_ref, tol)]
+    say("  fwd errors y/gvals/uvals: %.2e %.2e %.2e" % tuple(e))
+    if not bwd:
+        return
+    dx, dwg, dwu, dwd = moc.moc_ffn_bwd(Gd["x"], Gd["wg"], Gd["wu"], Gd["wd"], idx, gvals, uvals, Gd["dy"])
+    torch.cuda.synchronize()
+    ref = P.oracle_backward_for(L, idx_np, P.to_np(gvals), P.to_np(uvals))
+    errs = [P.assert_close(n, P.to_np(g), r, tol) for n, g, r in zip(("dx", "dwg", "dwu", "dwd"), (dx, dwg, dwu, dwd), ref)]
+    say("  bwd errors dx/dwg/dwu/dwd: %.2e %.2e %.2e %.2e" % tuple(errs))
+
+
+@pytest.mark.parametrize("T,d,F,a,b,dtype", [
+    (256, 512, 1376, 2, 8, "f32"),        # cfg0's shape
+    (100, 96, 200, 1, 4, "bf16"),         # ragged tiles, F not a multiple of 64
+    (70, 64, 48, 3, 16, "f32"),
+    (33, 128, 64, 8, 8, "bf16"),          # a = b: dense SwiGLU
+])
+def test_grouped_small_shapes(T, d, F, a, b, dtype):
+    run_grouped_fwd_bwd("small", 95, T, d, F, a, b, dtype)
+
+
+def test_grouped_cfg1_shape_2_of_8():
+    c = CONFIGS["cfg1"]
+    run_grouped_fwd_bwd("cfg1", 1, c.T, c.d, c.F, 2, 8, "bf16")
+
+
+def test_grouped_1b_shape_2_of_8_full_size():
+    # the 1B shape with d_ffn rounded up to a multiple of 8 (5461 -> 5464)
+    c = CONFIGS["cfg2"]
+    run_grouped_fwd_bwd("cfg2-like", 2, c.T, c.d, 5464, 2, 8, "bf16")
+
+
+def run_grouped_decode(tag, cfg_index, B, d, F, a, b, dtype, x_seed_offset=0):
+    K = F // b * a
+    say("[case] %s grouped decode %d:%d B=%d d=%d F=%d K=%d %s" % (tag, a, b, B, d, F, K, dtype))
+    tol = P.TOL[dtype]
+    L = inputs.make_layer(cfg_index, B, d, F, dtype, x_seed_offset=x_seed_offset)
+    Gd = gpu_layer(L, dtype)
+    y, idx = moc.moc_ffn_decode_grouped(Gd["x"], Gd["wg"], Gd["wu"], Gd["wd"], a, b)
+    torch.cuda.synchronize()
+    idx_np = idx.cpu().numpy()
+    Wg, Wu, Wd = P.paper_weights(L)
+    X = L["x"].astype(np.float64)
+    window = P.check_grouped_index_sets(idx_np, X @ Wg, a, b)
+    y_ref, sets = O.moc_decode_grouped(X, Wg, Wu, Wd, a, b)
+    keep = np.setdiff1d(np.arange(B), window)
+    np.testing.assert_array_equal(idx_np[keep], sets[keep])
+    if keep.size:
+        P.assert_close("y", P.to_np(y)[keep], y_ref[keep], tol)
+    D, _, _, _ = P.oracle_forward_for(L, idx_np)
+    P.assert_close("y(given idx)", P.to_np(y), D, tol)
+    # the grouped training forward on the same rows picks the same channels and the same output
+    y_f, idx_f, _, _ = moc.moc_ffn_fwd_grouped(Gd["x"], Gd["wg"], Gd["wu"], Gd["wd"], a, b)
+    torch.cuda.synchronize()
+    same = (idx_f == idx).all(dim=1).cpu().numpy()
+    assert same[keep].all()
+    P.assert_close("decode vs fwd", P.to_np(y)[same], P.to_np(y_f)[same], 2 * tol)
+    y2, none = moc.moc_ffn_decode_grouped(Gd["x"], Gd["wg"], Gd["wu"], Gd["wd"], a, b, want_idx=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(y2, y)
+
+
+@pytest.mark.parametrize("B,a,b", [(1, 2, 8), (4, 2, 8), (16, 2, 8), (1, 1, 8), (16, 1, 8)])
+def test_grouped_decode_7b_shape(B, a, b):
+    c = CONFIGS["cfg3"]
+    run_grouped_decode("cfg3", 3, B, c.d, c.F, a, b, "bf16", x_seed_offset=B)
+
+
+@pytest.mark.parametrize("B,d,F,a,b,dtype", [(3, 64, 96, 1, 4, "bf16"), (16, 256, 520, 2, 8, "bf16"), (2, 36, 48, 16, 16, "f32"),
+                                             (7, 512, 1376, 2, 8, "f32"), (9, 1024, 336, 3, 16, "bf16"),
+                                             (16, 2048, 1000, 1, 4, "bf16"), (5, 1024, 1040, 2, 8, "bf16")])
+def test_grouped_decode_small_shapes(B, d, F, a, b, dtype):
+    run_grouped_decode("small", 96, B, d, F, a, b, dtype)
