@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
+    ap.add_argument("--no-grouped", action="store_true", help="skip the MoC 2:8 (grouped Top-K) legs")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="run only moc_residual_add on 2 x 512 MiB (known traffic: 1 GiB read, 512 MiB written per "
@@ -194,6 +195,14 @@ def main():
     if not args.no_stack:
         stack = stack_leg(torch, moc, CONFIGS["cfg4"], dev)
 
+    # MoC_{2:8} (grouped Top-K): training step at the 1B shape with d_ff rounded up to a multiple of 8,
+    # and cold decode at the 7B shape
+    grouped = None
+    if not args.no_grouped:
+        grouped = {"train": grouped_train_leg(torch, moc, inputs, cfg, 2, 8, args.steps, args.warmup, dev),
+                   "decode": decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, group=(2, 8)),
+                   "decode_1of8": decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, group=(1, 8))}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
@@ -206,7 +215,7 @@ def main():
         "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
                    "T": T, "d_model": d, "d_ff": F, "K": K},
         "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
-        "decode": decode, "prefill_stack_layer": stack,
+        "decode": decode, "prefill_stack_layer": stack, "grouped_2of8": grouped,
     }
     print(json.dumps(line))
 
@@ -257,9 +266,65 @@ def stack_leg(torch, moc, cfg, dev):
             "residual_add_GBs": round(3 * row_bytes / (kern["residual_add"] * 1e-3) / 1e9, 1) if "residual_add" in kern else None}
 
 
-def decode_leg(torch, moc, inputs, cfg, batches, dev):
-    d, F, K = cfg.d, cfg.F, cfg.K
+def grouped_train_leg(torch, moc, inputs, cfg, a, b, steps, warmup, dev):
+    """Forward (grouped selection) + backward of one MoC_{a:b} layer; d_ff rounded up to a multiple of b."""
+    T, d = cfg.T, cfg.d
+    F = (cfg.F + b - 1) // b * b
+    K = F // b * a
     bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(50_000)
+    x = torch.randn((T, d), generator=gen, device=dev, dtype=torch.float32).to(bf)
+    dy = torch.randn((T, d), generator=gen, device=dev, dtype=torch.float32).to(bf)
+    w = [(torch.randn((F, d), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(bf) for _ in range(3)]
+    ws_f = torch.empty(moc.workspace_bytes(T, d, F, K, bf, 0), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(moc.workspace_bytes(T, d, F, K, bf, 1), dtype=torch.uint8, device=dev)
+    out_f = (torch.empty((T, d), dtype=bf, device=dev), torch.empty((T, K), dtype=torch.int32, device=dev),
+             torch.empty((T, K), dtype=bf, device=dev), torch.empty((T, K), dtype=bf, device=dev))
+    out_b = (torch.empty((T, d), dtype=bf, device=dev), torch.empty((F, d), dtype=bf, device=dev),
+             torch.empty((F, d), dtype=bf, device=dev), torch.empty((F, d), dtype=bf, device=dev))
+
+    def step():
+        y, idx, gv, uv = moc.moc_ffn_fwd_grouped(x, w[0], w[1], w[2], a, b, ws=ws_f, out=out_f)
+        moc.moc_ffn_bwd(x, w[0], w[1], w[2], idx, gv, uv, dy, ws=ws_b, out=out_b)
+
+    for _ in range(max(2, warmup // 2)):
+        step()
+    torch.cuda.synchronize()
+    n = max(3, steps // 2)
+    t0 = time.perf_counter()
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    moc.timing_reset()
+    moc.timing_enable(True)
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    kern = {k: round(v / max(c, 1), 4) for k, (v, c) in moc.timing_read().items()}
+    moc.timing_enable(False)
+    moc.timing_reset()
+    sel_bytes = T * (4 * F + 2 * F + 2 * ((F + 63) // 64 * 64) + K * (4 + 2 + 2))     # G, U in; Z' and the stored set out
+    sel = kern.get("group_select_act")
+    return {"workload": "1B shape, MoC %d:%d: T=%d d_model=%d d_ff=%d K=%d bf16" % (a, b, T, d, F, K),
+            "ms_per_step": round(ms, 4), "tokens_per_s": round(T / (ms * 1e-3), 1), "kernels_ms": kern,
+            "group_select_GBs": round(sel_bytes / (sel * 1e-3) / 1e9, 1) if sel else None,
+            "group_select_frac_hbm_peak": round(sel_bytes / (sel * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if sel else None}
+
+
+def decode_leg(torch, moc, inputs, cfg, batches, dev, group=None):
+    d, F, K = cfg.d, cfg.F, cfg.K
+    if group is not None:
+        K = F // group[1] * group[0]
+    bf = torch.bfloat16
+
+    def decode(x, w, ws, out):
+        if group is None:
+            moc.moc_ffn_decode(x, *w, K, ws=ws, out=out)
+        else:
+            moc.moc_ffn_decode_grouped(x, *w, group[0], group[1], ws=ws, out=out)
+
     R = 8        # independent weight sets: 8 x 270 MB >> the 256 MB last-level cache, so every call is cold
     gen = torch.Generator(device=dev)
     gen.manual_seed(30_000)
@@ -275,7 +340,7 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
         idx = torch.empty((B, K), dtype=torch.int32, device=dev)
         unions = []
         for r in range(R):
-            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+            decode(xs[r], sets[r], ws, (y, idx))
             torch.cuda.synchronize()
             unions.append(int(torch.unique(idx).numel()))
         union = float(np.mean(unions))
@@ -286,7 +351,7 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
         for i in range(iters):
             r = i % R
             start[i].record()
-            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+            decode(xs[r], sets[r], ws, (y, idx))
             stop[i].record()
         torch.cuda.synchronize()
         us = sorted(s.elapsed_time(e) * 1e3 for s, e in zip(start, stop))
@@ -296,19 +361,19 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
         moc.timing_enable(True)
         for i in range(2 * R):
             r = i % R
-            moc.moc_ffn_decode(xs[r], *sets[r], K, ws=ws, out=(y, idx))
+            decode(xs[r], sets[r], ws, (y, idx))
         torch.cuda.synchronize()
         kern_us = {k: round(ms * 1e3 / max(n, 1), 2) for k, (ms, n) in moc.timing_read().items()}
         moc.timing_enable(False)
         moc.timing_reset()
         # warm: the same weight set every call (cache-resident, reported separately)
         for _ in range(3):
-            moc.moc_ffn_decode(xs[0], *sets[0], K, ws=ws, out=(y, idx))
+            decode(xs[0], sets[0], ws, (y, idx))
         torch.cuda.synchronize()
         s0, e0 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s0.record()
         for _ in range(20):
-            moc.moc_ffn_decode(xs[0], *sets[0], K, ws=ws, out=(y, idx))
+            decode(xs[0], sets[0], ws, (y, idx))
         e0.record()
         torch.cuda.synchronize()
         warm_us = s0.elapsed_time(e0) * 1e3 / 20
@@ -317,7 +382,9 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev):
                     "union_channels": round(union, 1), "algorithmic_MB": round(algo_bytes / 1e6, 2),
                     "effective_GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
                     "kernels_us": kern_us})
-    return {"workload": "cfg3: d_model=%d d_ff=%d K=%d bf16, cold weights (8 rotating sets)" % (d, F, K), "batches": out}
+    sel = "row-wide Top-K" if group is None else "grouped Top-K %d:%d" % group
+    return {"workload": "cfg3: d_model=%d d_ff=%d K=%d bf16, %s, cold weights (8 rotating sets)" % (d, F, K, sel),
+            "batches": out}
 
 
 def cpu_baseline(L, K, sample_tokens):

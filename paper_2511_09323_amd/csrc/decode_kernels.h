@@ -441,6 +441,167 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
     }
 }
 
+// Whole decode step of MoC_{a:8} (a = GA = 1 or 2) in one launch, for up to BT tokens.  The grouped
+// selection is local to 8 consecutive channels, so a workgroup that has computed the gate values of
+// a group knows the group's kept channels at once and can fetch their W_up / W_down rows itself: no
+// launch boundary between gate, selection and gather.  512 threads; per group
+//   gate:   wave w reads row 8q + w of W_gate (prefetched during the previous group) and reduces its
+//           dot products with the BT staged tokens;
+//   select: after one barrier every thread ranks the 8 x BT gate values (same rule as
+//           group_select_kernel) and knows the BT*GA (token, channel) pairs;
+//   gather: wave w reads slice w (d/8 elements) of both rows of every pair, together with the next
+//           group's gate row; partial dots with x meet in LDS (second barrier); then
+//           acc[token][own columns] += SiLU(g) u W_down[j][own columns].
+// part[p, b, :] gets the workgroup's partial output (p = blockIdx.x); decode_reduce_kernel sums them.
+// Needs d % CN == 0 and d <= 8 * 64 * CN (one 16-byte chunk per lane and slice).
+template <class E, int BT, int GA>
+__global__ __launch_bounds__(512) void decode_fused_group_kernel(const E* __restrict__ x, const E* __restrict__ wg,
+                                                                 const E* __restrict__ wu, const E* __restrict__ wd,
+                                                                 int B, int d, int F, int K, int32_t* __restrict__ idx,
+                                                                 float* __restrict__ part) {
+    constexpr int CN = Chunk<E>::N;
+    constexpr int GB = 8, NWV = 8, NE = BT * GA;
+    constexpr int UN = 8;                       // 16-byte chunks of a gate row per lane
+    extern __shared__ __align__(16) unsigned char dec_smem[];
+    E* xs = reinterpret_cast<E*>(dec_smem);     // [BT][d]
+    __shared__ float gl[2][GB][BT];
+    __shared__ float dl[2][NE][NWV];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ngroups = F / GB;
+    int q = blockIdx.x;
+    u32x4_t raw[UN];
+    auto fetch_gate = [&](int qq) {
+        const E* wrow = wg + (int64_t)(qq * GB + wave) * d;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = (u * 64 + lane) * CN;
+            raw[u] = u32x4_t{0, 0, 0, 0};
+            if (k < d) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + k));
+        }
+    };
+    if (q < ngroups) fetch_gate(q);             // in flight while x is staged
+    for (int i = tid * CN; i < BT * d; i += 512 * CN) {
+        const int b = i / d;
+        u32x4_t v = {0, 0, 0, 0};
+        if (b < B) v = *reinterpret_cast<const u32x4_t*>(x + i);
+        *reinterpret_cast<u32x4_t*>(xs + i) = v;
+    }
+    __syncthreads();
+    const int kslice = (wave * 64 + lane) * CN;  // this thread's columns in the gather stage
+    const bool have_slice = kslice < d;
+    float acc[BT][CN];
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int e = 0; e < CN; ++e) acc[b][e] = 0.0f;
+    int it = 0;
+    for (; q < ngroups; q += gridDim.x, ++it) {
+        // ---- gate values of this wave's row for every token
+        float ga_[BT];
+#pragma unroll
+        for (int b = 0; b < BT; ++b) ga_[b] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = (u * 64 + lane) * CN;
+            if (k < d) {
+                float w[CN];
+                Chunk<E>::unpack(raw[u], w);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    float xv[CN];
+                    Chunk<E>::load(xs + b * d + k, xv);
+#pragma unroll
+                    for (int e = 0; e < CN; ++e) ga_[b] = fmaf(w[e], xv[e], ga_[b]);
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const float s = wave_sum(ga_[b]);
+            if (lane == 0) gl[it & 1][wave][b] = s;
+        }
+        __syncthreads();
+        // ---- selection (every thread, same result) and the loads that depend on it
+        int jsel[NE];
+        float gsel[NE];
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            float v[GB];
+#pragma unroll
+            for (int i = 0; i < GB; ++i) v[i] = gl[it & 1][i][b];
+            int rank[GB];
+            group_ranks<GB>(v, rank);
+#pragma unroll
+            for (int r = 0; r < GA; ++r) { jsel[b * GA + r] = q * GB; gsel[b * GA + r] = 0.0f; }
+#pragma unroll
+            for (int i = 0; i < GB; ++i) {
+                // kept channels in ascending order: the number of kept channels below i is the slot
+                int below = 0;
+#pragma unroll
+                for (int j = 0; j < GB; ++j)
+                    if (j < i) below += (rank[j] < GA) ? 1 : 0;
+#pragma unroll
+                for (int r = 0; r < GA; ++r)
+                    if (rank[i] < GA && below == r) { jsel[b * GA + r] = q * GB + i; gsel[b * GA + r] = v[i]; }
+            }
+        }
+        if (tid < B * GA) {
+            // tid = b * GA + r
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                if (tid == e) idx[(int64_t)(e / GA) * K + q * GA + (e % GA)] = jsel[e];
+        }
+        u32x4_t ru[NE], rd[NE];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            ru[e] = u32x4_t{0, 0, 0, 0};
+            rd[e] = u32x4_t{0, 0, 0, 0};
+            if (have_slice && e / GA < B) {
+                ru[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wu + (int64_t)jsel[e] * d + kslice));
+                rd[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wd + (int64_t)jsel[e] * d + kslice));
+            }
+        }
+        if (q + (int)gridDim.x < ngroups) fetch_gate(q + gridDim.x);     // next group's gate row, in flight with the gather
+        // ---- partial dots of the up projection over this wave's slice
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            float dot = 0.0f;
+            if (have_slice) {
+                float w[CN], xv[CN];
+                Chunk<E>::unpack(ru[e], w);
+                Chunk<E>::load(xs + (e / GA) * d + kslice, xv);
+#pragma unroll
+                for (int c = 0; c < CN; ++c) dot = fmaf(w[c], xv[c], dot);
+            }
+            dot = wave_sum(dot);
+            if (lane == 0) dl[it & 1][e][wave] = dot;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            float u = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NWV; ++w) u += dl[it & 1][e][w];
+            const float zz = silu_f32(gsel[e]) * u;
+            float w[CN];
+            Chunk<E>::unpack(rd[e], w);
+#pragma unroll
+            for (int c = 0; c < CN; ++c) acc[e / GA][c] = fmaf(zz, w[c], acc[e / GA][c]);
+        }
+    }
+    if (have_slice) {
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            if (b < B) {
+                float* dst = part + ((int64_t)blockIdx.x * B + b) * d + kslice;
+#pragma unroll
+                for (int c = 0; c < CN; c += 4)
+                    *reinterpret_cast<f32x4_t*>(dst + c) = f32x4_t{acc[b][c], acc[b][c + 1], acc[b][c + 2], acc[b][c + 3]};
+            }
+        }
+    }
+}
+
 // y[b, c] = sum_p part[p, b, c] in a fixed order (deterministic).  A 1024-thread workgroup owns 64
 // columns; its sixteen wavefronts each sum a sixteenth of the P partials with the loads in flight
 // together, and the sixteen sums are combined through LDS.

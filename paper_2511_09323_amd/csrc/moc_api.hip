@@ -311,6 +311,8 @@ int decode_splits(int B, int K) {
     return std::max(1, std::min(by_batch, by_k));
 }
 
+constexpr int kDecodeFusedMaxP = 512;
+
 struct DecodeWs {
     float *g, *gsel, *z, *part;
     int32_t* idx;
@@ -321,7 +323,9 @@ struct DecodeWs {
         gsel = c.take<float>((size_t)D.T * D.K);
         z = c.take<float>((size_t)D.T * D.K);
         idx = c.take<int32_t>((size_t)D.T * D.K);
-        part = c.take<float>((size_t)decode_splits(D.T, D.K) * D.T * D.d);
+        // partial outputs: one per channel share, or one per workgroup of the single-launch grouped kernel
+        const int shares = std::max(decode_splits(D.T, D.K), D.T <= 4 ? kDecodeFusedMaxP : 0);
+        part = c.take<float>((size_t)shares * D.T * D.d);
         bytes = c.off;
     }
 };
@@ -491,6 +495,34 @@ moc_status launch_decode_gate_mfma(const Dims& D, const bf16_t* x, const bf16_t*
     return MOC_OK;
 }
 
+template <class E, int BT, int GA>
+moc_status launch_decode_fused_t(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, int32_t* idx,
+                                 float* part, int P, hipStream_t st) {
+    const size_t lds = (size_t)BT * D.d * sizeof(E);
+    auto kern = decode_fused_group_kernel<E, BT, GA>;
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    64 * 1024));
+        attr = true;
+    }
+    Span span("decode_fused_gate_select_gather", st);
+    hipLaunchKernelGGL(kern, dim3(P), dim3(512), lds, st, x, wg, wu, wd, D.T, D.d, D.F, D.K, idx, part);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E>
+moc_status launch_decode_fused(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, int ga, int32_t* idx,
+                               float* part, int P, hipStream_t st) {
+    if (D.T == 1) {
+        if (ga == 1) return launch_decode_fused_t<E, 1, 1>(D, x, wg, wu, wd, idx, part, P, st);
+        return launch_decode_fused_t<E, 1, 2>(D, x, wg, wu, wd, idx, part, P, st);
+    }
+    if (ga == 1) return launch_decode_fused_t<E, 4, 1>(D, x, wg, wu, wd, idx, part, P, st);
+    return launch_decode_fused_t<E, 4, 2>(D, x, wg, wu, wd, idx, part, P, st);
+}
+
 // ga:gb = 0:0 is the row-wide Top-K; otherwise the grouped selection of MoC_{a:b}, which is decided
 // inside the gate kernel (a group's channels meet in one workgroup) and needs no selection launch.
 template <class E>
@@ -500,6 +532,21 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     const int B = D.T;
     int32_t* idx = idx_out ? idx_out : W.idx;
     moc_status s;
+    // MOC_DECODE_FUSED=0 (read at every call) keeps grouped decode on the separate gate+select and gather
+    // launches; MOC_DECODE_FUSED_P=n sets the workgroup count of the single-launch kernel.
+    if (gb == 8 && (ga == 1 || ga == 2) && B <= 4 && D.d <= 8 * 64 * Chunk<E>::N && env_int("MOC_DECODE_FUSED", 1) &&
+        !options().force_generic) {
+        // MoC_{a:8}: gate, selection and gather in one launch, then the deterministic reduction.
+        // Two resident workgroups per CU for one token, one for up to four (register budget).
+        const int want = env_int("MOC_DECODE_FUSED_P", B == 1 ? 512 : 256);
+        const int P = std::min(D.F / 8, std::max(1, std::min(kDecodeFusedMaxP, want)));
+        if ((s = launch_decode_fused<E>(D, x, wg, wu, wd, ga, idx, W.part, P, st)) != MOC_OK) return s;
+        Span span("decode_reduce", st);
+        const int64_t n = (int64_t)B * D.d;
+        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 63) / 64)), dim3(1024), 0, st, W.part, P, n, y);
+        HIP_TRY(hipGetLastError());
+        return MOC_OK;
+    }
     const size_t mfma_lds = (size_t)16 * (D.d * 2 + 16) + 4 * 4 * 256 * sizeof(float);
     const bool mfma_gate = B > 4 && std::is_same<E, bf16_t>::value && D.d % 1024 == 0 && mfma_lds <= 160 * 1024 - 64 &&
                            !options().force_generic;

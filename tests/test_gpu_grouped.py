@@ -152,8 +152,17 @@ def test_grouped_decode_7b_shape(B, a, b):
     run_grouped_decode("cfg3", 3, B, c.d, c.F, a, b, "bf16", x_seed_offset=B)
 
 
-@pytest.mark.parametrize("B,d,F,a,b,dtype", [(3, 64, 96, 1, 4, "bf16"), (16, 256, 520, 2, 8, "bf16"), (2, 36, 48, 16, 16, "f32"),
+@pytest.mark.parametrize("B,d,F,a,b,dtype", [(1, 64, 96, 2, 8, "bf16"), (3, 200, 104, 1, 8, "f32"), (4, 4096, 1000, 2, 8, "bf16"),
+                                             (2, 2048, 520, 2, 8, "f32"), (2, 4096, 64, 1, 8, "f32"), (4, 8, 8, 2, 8, "bf16"),
+                                             (3, 64, 96, 1, 4, "bf16"), (16, 256, 520, 2, 8, "bf16"), (2, 36, 48, 16, 16, "f32"),
                                              (7, 512, 1376, 2, 8, "f32"), (9, 1024, 336, 3, 16, "bf16"),
                                              (16, 2048, 1000, 1, 4, "bf16"), (5, 1024, 1040, 2, 8, "bf16")])
 def test_grouped_decode_small_shapes(B, d, F, a, b, dtype):
     run_grouped_decode("small", 96, B, d, F, a, b, dtype)
+
+
+@pytest.mark.parametrize("B,a", [(1, 2), (4, 2), (2, 1)])
+def test_grouped_decode_separate_launches_match_too(B, a, monkeypatch):
+    # the gate+select / gather / reduce launches that batches above four (and other a:b) use
+    monkeypatch.setenv("MOC_DECODE_FUSED", "0")
+    run_grouped_decode("unfused", 97, B, 1024, 2048, a, 8, "bf16")
