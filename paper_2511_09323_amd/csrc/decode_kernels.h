@@ -441,7 +441,8 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
     }
 }
 
-// Whole decode step of MoC_{a:8} (a = GA = 1 or 2) in one launch, for up to BT tokens.  The grouped
+// Whole decode step of MoC_{a:8} (a = GA = 1 or 2) in one launch, for up to BT tokens (the host uses it
+// for single tokens only: with more tokens per workgroup the separate launches measured faster).  The grouped
 // selection is local to 8 consecutive channels, so a workgroup that has computed the gate values of
 // a group knows the group's kept channels at once and can fetch their W_up / W_down rows itself: no
 // launch boundary between gate, selection and gather.  512 threads; per group
@@ -461,6 +462,7 @@ __global__ __launch_bounds__(512) void decode_fused_group_kernel(const E* __rest
                                                                  float* __restrict__ part) {
     constexpr int CN = Chunk<E>::N;
     constexpr int GB = 8, NWV = 8, NE = BT * GA;
+    static_assert(GA == 1 || GA == 2, "the ordered pair below covers one or two kept channels");
     constexpr int UN = 8;                       // 16-byte chunks of a gate row per lane
     extern __shared__ __align__(16) unsigned char dec_smem[];
     E* xs = reinterpret_cast<E*>(dec_smem);     // [BT][d]
@@ -531,18 +533,27 @@ __global__ __launch_bounds__(512) void decode_fused_group_kernel(const E* __rest
             for (int i = 0; i < GB; ++i) v[i] = gl[it & 1][i][b];
             int rank[GB];
             group_ranks<GB>(v, rank);
-#pragma unroll
-            for (int r = 0; r < GA; ++r) { jsel[b * GA + r] = q * GB; gsel[b * GA + r] = 0.0f; }
+            // kept channels in ascending order: with GA <= 2 they are the lowest and the highest kept index
+            int lo = -1, hi = 0;
 #pragma unroll
             for (int i = 0; i < GB; ++i) {
-                // kept channels in ascending order: the number of kept channels below i is the slot
-                int below = 0;
+                if (rank[i] < GA) {
+                    if (lo < 0) lo = i;
+                    hi = i;
+                }
+            }
+            if (lo < 0) lo = 0;                                  // only for non-finite input
+            float vlo = v[0], vhi = v[0];
 #pragma unroll
-                for (int j = 0; j < GB; ++j)
-                    if (j < i) below += (rank[j] < GA) ? 1 : 0;
-#pragma unroll
-                for (int r = 0; r < GA; ++r)
-                    if (rank[i] < GA && below == r) { jsel[b * GA + r] = q * GB + i; gsel[b * GA + r] = v[i]; }
+            for (int i = 1; i < GB; ++i) {
+                vlo = (i == lo) ? v[i] : vlo;
+                vhi = (i == hi) ? v[i] : vhi;
+            }
+            jsel[b * GA] = q * GB + lo;
+            gsel[b * GA] = vlo;
+            if (GA == 2) {
+                jsel[b * GA + 1] = q * GB + hi;
+                gsel[b * GA + 1] = vhi;
             }
         }
         if (tid < B * GA) {

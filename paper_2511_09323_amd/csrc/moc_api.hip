@@ -324,7 +324,7 @@ struct DecodeWs {
         z = c.take<float>((size_t)D.T * D.K);
         idx = c.take<int32_t>((size_t)D.T * D.K);
         // partial outputs: one per channel share, or one per workgroup of the single-launch grouped kernel
-        const int shares = std::max(decode_splits(D.T, D.K), D.T <= 4 ? kDecodeFusedMaxP : 0);
+        const int shares = std::max(decode_splits(D.T, D.K), D.T == 1 ? kDecodeFusedMaxP : 0);
         part = c.take<float>((size_t)shares * D.T * D.d);
         bytes = c.off;
     }
@@ -515,12 +515,8 @@ moc_status launch_decode_fused_t(const Dims& D, const E* x, const E* wg, const E
 template <class E>
 moc_status launch_decode_fused(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, int ga, int32_t* idx,
                                float* part, int P, hipStream_t st) {
-    if (D.T == 1) {
-        if (ga == 1) return launch_decode_fused_t<E, 1, 1>(D, x, wg, wu, wd, idx, part, P, st);
-        return launch_decode_fused_t<E, 1, 2>(D, x, wg, wu, wd, idx, part, P, st);
-    }
-    if (ga == 1) return launch_decode_fused_t<E, 4, 1>(D, x, wg, wu, wd, idx, part, P, st);
-    return launch_decode_fused_t<E, 4, 2>(D, x, wg, wu, wd, idx, part, P, st);
+    if (ga == 1) return launch_decode_fused_t<E, 1, 1>(D, x, wg, wu, wd, idx, part, P, st);
+    return launch_decode_fused_t<E, 1, 2>(D, x, wg, wu, wd, idx, part, P, st);
 }
 
 // ga:gb = 0:0 is the row-wide Top-K; otherwise the grouped selection of MoC_{a:b}, which is decided
@@ -534,12 +530,14 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     moc_status s;
     // MOC_DECODE_FUSED=0 (read at every call) keeps grouped decode on the separate gate+select and gather
     // launches; MOC_DECODE_FUSED_P=n sets the workgroup count of the single-launch kernel.
-    if (gb == 8 && (ga == 1 || ga == 2) && B <= 4 && D.d <= 8 * 64 * Chunk<E>::N && env_int("MOC_DECODE_FUSED", 1) &&
+    if (gb == 8 && (ga == 1 || ga == 2) && B == 1 && D.d <= 8 * 64 * Chunk<E>::N && env_int("MOC_DECODE_FUSED", 1) &&
         !options().force_generic) {
-        // MoC_{a:8}: gate, selection and gather in one launch, then the deterministic reduction.
-        // Two resident workgroups per CU for one token, one for up to four (register budget).
-        const int want = env_int("MOC_DECODE_FUSED_P", B == 1 ? 512 : 256);
-        const int P = std::min(D.F / 8, std::max(1, std::min(kDecodeFusedMaxP, want)));
+        // MoC_{a:8}, one token: gate, selection and gather in one launch, then the deterministic
+        // reduction.  Two workgroups are resident per CU; the groups are dealt out evenly.
+        const int ngroups = D.F / 8;
+        const int rounds = (ngroups + kDecodeFusedMaxP - 1) / kDecodeFusedMaxP;
+        const int want = env_int("MOC_DECODE_FUSED_P", (ngroups + rounds - 1) / rounds);
+        const int P = std::min(ngroups, std::max(1, std::min(kDecodeFusedMaxP, want)));
         if ((s = launch_decode_fused<E>(D, x, wg, wu, wd, ga, idx, W.part, P, st)) != MOC_OK) return s;
         Span span("decode_reduce", st);
         const int64_t n = (int64_t)B * D.d;
