@@ -42,8 +42,23 @@ typedef GemmProblem<bf16_t> MfmaProblem;
 constexpr int kMfmaBK = 32;
 constexpr int kMfmaStages = 3;
 
+#ifdef MOC_KC_PITCH80
+constexpr bool kKcSwizzle = false;
+#else
+constexpr bool kKcSwizzle = true;
+#endif
+
+// LDS byte offset of the 16-byte chunk `ch` (8 k) of row `row` in a k-contiguous tile: rows of 64
+// bytes, chunk position XORed with bits 2..3 of the row.  Both the staging writes (16 lanes = 4
+// rows x 4 chunks) and the fragment reads (16 lanes = 16 rows, one chunk) then hit 16 different
+// 16-byte bank groups.
+__device__ __forceinline__ int kc_lds_offset(int row, int ch) {
+    if (kKcSwizzle) return row * 64 + ((ch ^ ((row >> 2) & 3)) << 4);
+    return row * 80 + ch * 16;
+}
+
 template <int ROWS, bool KM> struct OperandTile {
-    static constexpr int kPitch = KM ? (ROWS * 2 + 64) : (kMfmaBK * 2 + 16);   // bytes
+    static constexpr int kPitch = KM ? (ROWS * 2 + 64) : (kKcSwizzle ? kMfmaBK * 2 : kMfmaBK * 2 + 16);   // bytes
     static constexpr int kBytes = KM ? kMfmaBK * kPitch : ROWS * kPitch;
     static constexpr int kChunks = ROWS * kMfmaBK / 8 / 256;                    // 16-byte chunks per thread
 };
@@ -61,8 +76,7 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 template <bool KM, int PITCH>
 __device__ __forceinline__ bf16x8_t read_fragment(const unsigned char* tile, int row0, int kk, int lane) {
     if (!KM) {
-        const unsigned char* p = tile + (row0 + (lane & 31)) * PITCH + (kk * 16 + 8 * (lane >> 5)) * 2;
-        return *reinterpret_cast<const bf16x8_t*>(p);
+        return *reinterpret_cast<const bf16x8_t*>(tile + kc_lds_offset(row0 + (lane & 31), kk * 2 + (lane >> 5)));
     } else {
         // 16-lane groups: lanes 4q..4q+3 of a group address k-row q (4 x 8 bytes = 16 rows); the
         // transposing read hands lane i of the group the 4 k-values of row i.
@@ -138,7 +152,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
         if (!AKM) {
             const int row = c >> 2, ch = c & 3;
             a_off[i] = min(m0 + row, M - 1) * (int)pr.A.ld + ch * 8;
-            a_lds[i] = row * TA::kPitch + ch * 16;
+            a_lds[i] = kc_lds_offset(row, ch);
             a_k[i] = ch * 8;
         } else {
             const int krow = c / (BM / 8), ch = c % (BM / 8);
@@ -153,7 +167,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
         if (!BKM) {
             const int row = c >> 2, ch = c & 3;
             b_off[i] = min(n0 + row, N - 1) * (int)pr.B.ld + ch * 8;
-            b_lds[i] = TA::kBytes + row * TB::kPitch + ch * 16;
+            b_lds[i] = TA::kBytes + kc_lds_offset(row, ch);
             b_k[i] = ch * 8;
         } else {
             const int krow = c / (BN / 8), ch = c % (BN / 8);
