@@ -20,6 +20,12 @@ template <> struct Chunk<float> {
     static __device__ __forceinline__ void load(const float* p, float* v) {
         unpack(*reinterpret_cast<const u32x4_t*>(p), v);
     }
+    // acc + sum of the products of the elements of two chunks
+    static __device__ __forceinline__ float dot(u32x4_t a, u32x4_t b, float acc) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(a[i]), __uint_as_float(b[i]), acc);
+        return acc;
+    }
 };
 template <> struct Chunk<bf16_t> {
     static constexpr int N = 8;
@@ -32,6 +38,15 @@ template <> struct Chunk<bf16_t> {
     }
     static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
         unpack(*reinterpret_cast<const u32x4_t*>(p), v);
+    }
+    // (v_dot2c_f32_bf16 would halve the instruction count but measured slower here.)
+    static __device__ __forceinline__ float dot(u32x4_t a, u32x4_t b, float acc) {
+        float w[N], x[N];
+        unpack(a, w);
+        unpack(b, x);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc = fmaf(w[i], x[i], acc);
+        return acc;
     }
 };
 
@@ -70,15 +85,9 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
             for (int u = 0; u < UN; ++u) {
                 const int k = k0 + u * 64 * CN;
                 if (k < d) {
-                    float w[CN];
-                    Chunk<E>::unpack(raw[u], w);
 #pragma unroll
-                    for (int b = 0; b < BT; ++b) {
-                        float xv[CN];
-                        Chunk<E>::load(xs + b * d + k, xv);
-#pragma unroll
-                        for (int e = 0; e < CN; ++e) acc[b] = fmaf(w[e], xv[e], acc[b]);
-                    }
+                    for (int b = 0; b < BT; ++b)
+                        acc[b] = Chunk<E>::dot(raw[u], *reinterpret_cast<const u32x4_t*>(xs + b * d + k), acc[b]);
                 }
             }
         }
@@ -150,15 +159,9 @@ __global__ __launch_bounds__(256) void decode_gate_group_kernel(const E* __restr
                 for (int u = 0; u < UN; ++u) {
                     const int k = k0 + u * 64 * CN;
                     if (k < d) {
-                        float w[CN];
-                        Chunk<E>::unpack(raw[u], w);
 #pragma unroll
-                        for (int b = 0; b < BT; ++b) {
-                            float xv[CN];
-                            Chunk<E>::load(xs + b * d + k, xv);
-#pragma unroll
-                            for (int e = 0; e < CN; ++e) acc[b] = fmaf(w[e], xv[e], acc[b]);
-                        }
+                        for (int b = 0; b < BT; ++b)
+                            acc[b] = Chunk<E>::dot(raw[u], *reinterpret_cast<const u32x4_t*>(xs + b * d + k), acc[b]);
                     }
                 }
             }
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __r
     const int q = lane >> 4;                                         // 16-element k sub-block of a 64-wide step
     const bf16_t* wrow = wg + (int64_t)min(row0 + (lane & 15), F - 1) * d + ks * kq + q * 16;
     // first weights in flight before x is staged
-    constexpr int UN = 4;                                            // steps of 64 k in flight
+    constexpr int UN = 4;                                            // steps of 64 k in flight (8 measured slower)
     u32x4_t w0[UN], w1[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
@@ -352,19 +355,31 @@ __global__ __launch_bounds__(256) void decode_down_kernel(const E* __restrict__ 
 // Fused gather stage for one token per workgroup column: for the p-th share of token b's selected
 // channels, u = x[b] . wu[j], z' = SiLU(g) u, and part[p, b, :] = sum z' wd[j, :].  A wavefront
 // owns a channel at a time and has both of its rows (one of wu, one of wd, NIT 16-byte chunks per
-// lane each) in flight before it waits.  grid = (P, B), 512 threads; needs d <= 64 * CN * NIT.
-template <class E, int NIT>
+// lane each) in flight before it waits.  P * B workgroups of 512 threads; needs d <= 64 * CN * NIT.
+// Workgroup w of the P * B launched handles (share p, token b).  idx rows ascend, so share p of every
+// token covers about the same channel range: when P is a multiple of 8 the workgroups of one share
+// are placed on one XCD (w % 8), whose L2 then serves the rows that several tokens selected
+// (SHARED = true also drops the non-temporal hint so that those rows stay in L2).
+template <class E, int NIT, bool SHARED>
 __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict__ x, const E* __restrict__ wu,
                                                             const E* __restrict__ wd,
                                                             const int32_t* __restrict__ idx,
-                                                            const float* __restrict__ gsel, int d, int K, int P,
+                                                            const float* __restrict__ gsel, int d, int K, int P, int B,
                                                             float* __restrict__ part) {
     constexpr int CN = Chunk<E>::N;
     constexpr int NWV = 8;
     extern __shared__ __align__(16) unsigned char dec_smem[];
     E* xs = reinterpret_cast<E*>(dec_smem);
     float* red = reinterpret_cast<float*>(dec_smem + (size_t)d * sizeof(E));     // [NWV][d]
-    const int p = blockIdx.x, b = blockIdx.y;
+    int p, b;
+    if (SHARED && P % 8 == 0) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        p = xcd + 8 * (slot / B);
+        b = slot % B;
+    } else {
+        p = blockIdx.x / B;
+        b = blockIdx.x % B;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per = (K + P - 1) / P;
     const int s_begin = p * per, s_end = min(K, s_begin + per);
@@ -385,13 +400,15 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
         for (int i = 0; i < NIT; ++i) {
             const int k = i * 64 * CN + lane * CN;
             ru[i] = u32x4_t{0, 0, 0, 0};
-            if (k < d) ru[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(urow + k));
+            if (k < d) ru[i] = SHARED ? *reinterpret_cast<const u32x4_t*>(urow + k)
+                                      : __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(urow + k));
         }
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int k = i * 64 * CN + lane * CN;
             rd[i] = u32x4_t{0, 0, 0, 0};
-            if (k < d) rd[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(drow + k));
+            if (k < d) rd[i] = SHARED ? *reinterpret_cast<const u32x4_t*>(drow + k)
+                                      : __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(drow + k));
         }
     };
     int s = s_begin + wave;
@@ -405,11 +422,7 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
         for (int i = 0; i < NIT; ++i) {
             const int k = i * 64 * CN + lane * CN;
             if (k < d) {
-                float w[CN], xv[CN];
-                Chunk<E>::unpack(ru[i], w);
-                Chunk<E>::load(xs + k, xv);
-#pragma unroll
-                for (int e = 0; e < CN; ++e) dot = fmaf(w[e], xv[e], dot);
+                dot = Chunk<E>::dot(ru[i], *reinterpret_cast<const u32x4_t*>(xs + k), dot);
             }
         }
         dot = wave_sum(dot);
@@ -437,7 +450,7 @@ __global__ __launch_bounds__(512) void decode_updown_kernel(const E* __restrict_
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < NWV; ++w) s += red[w * d + c];
-        part[((int64_t)p * gridDim.y + b) * d + c] = s;
+        part[((int64_t)p * B + b) * d + c] = s;
     }
 }
 
@@ -506,15 +519,9 @@ __global__ __launch_bounds__(512) void decode_fused_group_kernel(const E* __rest
         for (int u = 0; u < UN; ++u) {
             const int k = (u * 64 + lane) * CN;
             if (k < d) {
-                float w[CN];
-                Chunk<E>::unpack(raw[u], w);
 #pragma unroll
-                for (int b = 0; b < BT; ++b) {
-                    float xv[CN];
-                    Chunk<E>::load(xs + b * d + k, xv);
-#pragma unroll
-                    for (int e = 0; e < CN; ++e) ga_[b] = fmaf(w[e], xv[e], ga_[b]);
-                }
+                for (int b = 0; b < BT; ++b)
+                    ga_[b] = Chunk<E>::dot(raw[u], *reinterpret_cast<const u32x4_t*>(xs + b * d + k), ga_[b]);
             }
         }
 #pragma unroll
@@ -578,11 +585,7 @@ __global__ __launch_bounds__(512) void decode_fused_group_kernel(const E* __rest
         for (int e = 0; e < NE; ++e) {
             float dot = 0.0f;
             if (have_slice) {
-                float w[CN], xv[CN];
-                Chunk<E>::unpack(ru[e], w);
-                Chunk<E>::load(xs + (e / GA) * d + kslice, xv);
-#pragma unroll
-                for (int c = 0; c < CN; ++c) dot = fmaf(w[c], xv[c], dot);
+                dot = Chunk<E>::dot(ru[e], *reinterpret_cast<const u32x4_t*>(xs + (e / GA) * d + kslice), dot);
             }
             dot = wave_sum(dot);
             if (lane == 0) dl[it & 1][e][wave] = dot;

@@ -303,10 +303,10 @@ template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mas
     }
 };
 
-// Channel shares per token in the gather stage: about one channel per wavefront (8 per workgroup)
-// for the smallest batches, fewer and longer shares as the batch grows.
+// Channel shares per token in the gather stage: shares x tokens fills the 256 CUs once (one
+// 512-thread workgroup per CU), and a multiple of 8 shares lets the kernel keep each share on one XCD.
 int decode_splits(int B, int K) {
-    const int by_batch = B <= 2 ? 256 : (B <= 4 ? 96 : (B <= 8 ? 48 : 24));
+    const int by_batch = std::max(8, 256 / B / 8 * 8);
     const int by_k = (K + 7) / 8;
     return std::max(1, std::min(by_batch, by_k));
 }
@@ -573,15 +573,15 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     constexpr int NIT = 8;
     const size_t fused_lds = (size_t)D.d * sizeof(E) + (size_t)8 * D.d * sizeof(float);
     if (D.d <= 64 * Chunk<E>::N * NIT && fused_lds <= 160 * 1024 - 64) {
-        auto kern = decode_updown_kernel<E, NIT>;
-        static bool attr = false;
-        if (!attr) {
+        auto kern = B > 1 ? decode_updown_kernel<E, NIT, true> : decode_updown_kernel<E, NIT, false>;
+        static bool attr[2] = {false, false};
+        if (!attr[B > 1]) {
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         160 * 1024 - 64));
-            attr = true;
+            attr[B > 1] = true;
         }
         Span span("decode_updown", st);
-        hipLaunchKernelGGL(kern, dim3(P, B), dim3(512), fused_lds, st, x, wu, wd, idx, W.gsel, D.d, D.K, P, W.part);
+        hipLaunchKernelGGL(kern, dim3(P * B), dim3(512), fused_lds, st, x, wu, wd, idx, W.gsel, D.d, D.K, P, B, W.part);
         HIP_TRY(hipGetLastError());
     } else {
         {
