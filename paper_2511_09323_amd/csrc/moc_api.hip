@@ -209,10 +209,20 @@ moc_status run_topk_lds(const char* name, const TopkArgs<E>& a, int T, hipStream
     return MOC_OK;
 }
 
+constexpr size_t kTopkRegDynMax = 96 * 1024;     // slot lists + dense row of the register-resident kernel
+
 template <class E, int NT, int NCH, bool FUSED>
 moc_status launch_topk_reg(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
+    const size_t dyn = topk_reg_dyn_lds(a.K, FUSED ? a.ldz : 0, sizeof(E), FUSED);
+    auto kern = topk_rows_kernel<E, NT, NCH, FUSED>;
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kTopkRegDynMax));
+        attr = true;
+    }
     Span span(name, st);
-    hipLaunchKernelGGL((topk_rows_kernel<E, NT, NCH, FUSED>), dim3(T), dim3(NT), 0, st, a);
+    hipLaunchKernelGGL(kern, dim3(T), dim3(NT), dyn, st, a);
     HIP_TRY(hipGetLastError());
     return MOC_OK;
 }
@@ -224,18 +234,21 @@ moc_status run_topk(const char* name, const TopkArgs<E>& a, int T, hipStream_t s
     const bool aligned = a.ldg % 4 == 0 && aligned16(a.g);
     const int cover = FUSED ? (int)std::max<int64_t>(a.F, a.ldz) : a.F;
     const int nch = (cover + NT * 4 - 1) / (NT * 4);
-    if (aligned) {
+    // very large K (slot lists beyond the LDS budget of the register kernel) goes to the LDS-resident kernel
+    const bool lists_fit = topk_reg_dyn_lds(a.K, FUSED ? a.ldz : 0, sizeof(E), FUSED) <= kTopkRegDynMax;
+    if (aligned && lists_fit) {
         if (nch <= 1) return launch_topk_reg<E, NT, 1, FUSED>(name, a, T, st);
         if (nch <= 2) return launch_topk_reg<E, NT, 2, FUSED>(name, a, T, st);
         if (nch <= 3) return launch_topk_reg<E, NT, 3, FUSED>(name, a, T, st);
-        if (NT == 256) {
+        if (NT == 256 || NT == 512) {
             if (nch <= 4) return launch_topk_reg<E, NT, 4, FUSED>(name, a, T, st);
             if (nch <= 6) return launch_topk_reg<E, NT, 6, FUSED>(name, a, T, st);
             if (nch <= 8) return launch_topk_reg<E, NT, 8, FUSED>(name, a, T, st);
-            if (nch <= 11) return launch_topk_reg<E, NT, 11, FUSED>(name, a, T, st);
+            if (NT == 256 && nch <= 11) return launch_topk_reg<E, NT, 11, FUSED>(name, a, T, st);
         }
         return run_topk_lds<E, NT, 4, FUSED>(name, a, T, st);
     }
+    if (aligned) return run_topk_lds<E, NT, 4, FUSED>(name, a, T, st);
     if (FUSED) return fail(MOC_ERR_BAD_ARG, "%s: unaligned workspace", name);
     return run_topk_lds<E, NT, 1, FUSED>(name, a, T, st);
 }
@@ -362,7 +375,11 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     if ((s = run_gemm<E, false, false>("gemm_up", pu, EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
-    if (gb == 0) s = run_topk<E, 256, true>("topk_select_act", a, D.T, st);
+    // 256 threads per row keep up to 24 values per thread in registers; longer rows get 512 threads
+    const int topk_nt = env_int("MOC_TOPK_NT", D.ldF > 6144 ? 512 : 256);
+    if (gb == 0) s = topk_nt == 1024  ? run_topk<E, 1024, true>("topk_select_act", a, D.T, st)
+                     : topk_nt == 512 ? run_topk<E, 512, true>("topk_select_act", a, D.T, st)
+                                      : run_topk<E, 256, true>("topk_select_act", a, D.T, st);
     else s = run_group_select<E, true>("group_select_act", a, D.T, ga, gb, st);      // MoC_{a:b}
     if (s != MOC_OK) return s;
     return down_projection<E>(D, W.Zd, wd, y, st);

@@ -272,12 +272,16 @@ __global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
 // the bins (meanwhile the other waves clear the histogram of the next pass).  Channels are ranked
 // with one ballot sweep whose per-lane prefixes stay in registers.  When all keys equal to the
 // threshold are selected (the usual case) a single ">= threshold" predicate is ranked; ties that
-// straddle the cut take the general path with a second predicate.
+// straddle the cut take the general path with a second predicate.  Selected channels are staged
+// in LDS at their output slot, so that the compact outputs are written slot by slot (coalesced,
+// SiLU evaluated K times instead of under divergence for every channel) and the dense Z' row is
+// assembled in LDS and streamed out with 16-byte stores.  Dynamic LDS: topk_reg_dyn_lds().
 template <class E, int NT, int NCH, bool FUSED>
 __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     constexpr int NW = NT / 64;
     constexpr int CHUNK = NT * 4;
-    __shared__ uint32_t hist[2][kTopkBins];
+    extern __shared__ __align__(16) unsigned char topk_dyn[];       // histograms, later slot lists + dense row
+    uint32_t (*hist)[kTopkBins] = reinterpret_cast<uint32_t (*)[kTopkBins]>(topk_dyn);
     __shared__ int tab_gt[NCH * NW], tab_eq[NCH * NW];
     __shared__ int red[NW];
     __shared__ uint32_t sh_prefix;
@@ -392,31 +396,41 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         cnt_eq = sh_cnt;
     }
     const uint32_t tau = prefix;
-    const bool all_ties = cnt_eq == need;        // every key equal to tau is selected
+    const bool all_ties = cnt_eq == need;        // every key equal to tau is selected (the usual case)
+    // "above" test as one unsigned compare: k >= thr.  Padding keys are 0 and every real key of a
+    // finite value is at least 0x007FFFFF, so padding never passes and needs no range check.
+    const uint32_t thr = tau + ((all_ties || tau == 0xFFFFFFFFu) ? 0u : 1u);
 
     // ---- one ballot sweep: per-lane prefixes in registers, per-wave totals to LDS
     int pg[NCH], pe[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        int lg = 0, le = 0, ngt = 0, neq = 0;
+        int lg = 0, ngt = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool in = c * CHUNK + tid * 4 + e < F;
-            const uint32_t k = key[c][e];
-            const uint64_t bg = __ballot(in && (all_ties ? k >= tau : k > tau));
+            const uint64_t bg = __ballot(key[c][e] >= thr);
             lg += mbcnt(bg);
             ngt += __popcll(bg);
-            if (!all_ties) {
-                const uint64_t be = __ballot(in && k == tau);
+        }
+        pg[c] = lg;
+        pe[c] = 0;
+        if (lane == 0) {
+            tab_gt[c * NW + wave] = ngt;
+            tab_eq[c * NW + wave] = 0;
+        }
+    }
+    if (!all_ties) {                               // ties straddle the cut: rank the equal keys too
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            int le = 0, neq = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint64_t be = __ballot(key[c][e] == tau);
                 le += mbcnt(be);
                 neq += __popcll(be);
             }
-        }
-        pg[c] = lg;
-        pe[c] = le;
-        if (lane == 0) {
-            tab_gt[c * NW + wave] = ngt;
-            tab_eq[c * NW + wave] = neq;
+            pe[c] = le;
+            if (lane == 0) tab_eq[c * NW + wave] = neq;
         }
     }
     __syncthreads();
@@ -446,16 +460,24 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             }
         }
     }
+    // ---- slot lists and the dense row take over the histogram memory (dead since the last pass)
+    int* l_idx = reinterpret_cast<int*>(topk_dyn);                     // [K]
+    float* l_g = reinterpret_cast<float*>(topk_dyn) + K;               // [K]
+    float* l_u = l_g + K;                                              // [K]   (FUSED)
+    E* zrow = reinterpret_cast<E*>(topk_dyn + ((size_t)3 * K * 4 + 15) / 16 * 16);   // [ldz] (FUSED)
+    const int ldz = FUSED ? (int)a.ldz : 0;
+    if (FUSED) {
+        constexpr int PER = 16 / (int)sizeof(E);
+        for (int i = tid * PER; i < ldz; i += NT * PER) *reinterpret_cast<u32x4_t*>(zrow + i) = u32x4_t{0, 0, 0, 0};
+    }
     __syncthreads();
 
-    // ---- rank and write
-    int32_t* idx_row = a.idx + row * K;
+    // ---- rank: every selected channel drops (channel, gate value, up value) into LDS at its
+    //      output slot (number of selected channels before it)
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int j0 = c * CHUNK + tid * 4;
-        int gt_before = tab_gt[c * NW + wave] + pg[c];
-        int eq_before = tab_eq[c * NW + wave] + pe[c];
-        float z[4], uu[4];
+        float uu[4];
         if (FUSED) {
             if (sizeof(E) == 2) {
                 uu[0] = __uint_as_float(uraw[c][0] << 16); uu[1] = __uint_as_float(uraw[c][0] & 0xFFFF0000u);
@@ -464,30 +486,67 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                 uu[0] = uf[c][0]; uu[1] = uf[c][1]; uu[2] = uf[c][2]; uu[3] = uf[c][3];
             }
         }
+        int gt_before = tab_gt[c * NW + wave] + pg[c];
+        if (all_ties) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = j0 + e < F;
-            const uint32_t k = key[c][e];
-            const bool isgt = in && (all_ties ? k >= tau : k > tau);
-            const bool iseq = in && !all_ties && k == tau;
-            const bool sel = isgt || (iseq && eq_before < need);
-            z[e] = 0.0f;
-            if (sel) {
-                const int slot = gt_before + min(eq_before, need);
-                const float g = key_float(k);
-                idx_row[slot] = j0 + e;
-                if (a.gsel_f32) a.gsel_f32[row * K + slot] = g;
-                if (a.gvals) Elem<E>::store(a.gvals + row * K + slot, g);
-                if (FUSED) {
-                    Elem<E>::store(a.uvals + row * K + slot, uu[e]);
-                    z[e] = silu_f32(g) * uu[e];
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t k = key[c][e];
+                if (k >= thr) {
+                    const int slot = min(gt_before, K - 1);
+                    l_idx[slot] = j0 + e;
+                    l_g[slot] = key_float(k);
+                    if (FUSED) l_u[slot] = uu[e];
+                    ++gt_before;
                 }
             }
-            gt_before += isgt ? 1 : 0;
-            eq_before += iseq ? 1 : 0;
+        } else {
+            int eq_before = tab_eq[c * NW + wave] + pe[c];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t k = key[c][e];
+                const bool isgt = k >= thr, iseq = k == tau;
+                if (isgt || (iseq && eq_before < need)) {
+                    const int slot = min(gt_before + min(eq_before, need), K - 1);
+                    l_idx[slot] = j0 + e;
+                    l_g[slot] = key_float(k);
+                    if (FUSED) l_u[slot] = uu[e];
+                }
+                gt_before += isgt ? 1 : 0;
+                eq_before += iseq ? 1 : 0;
+            }
         }
-        if (FUSED && j0 < a.ldz) store_vec4_any<E>(a.zd + row * a.ldz + j0, z);
     }
+    __syncthreads();
+    // ---- write the compact outputs slot by slot (coalesced) and scatter z' into the dense row
+    for (int sl = tid; sl < K; sl += NT) {
+        const int j = l_idx[sl];
+        const float g = l_g[sl];
+        a.idx[row * K + sl] = j;
+        if (a.gsel_f32) a.gsel_f32[row * K + sl] = g;
+        if (a.gvals) Elem<E>::store(a.gvals + row * K + sl, g);
+        if (FUSED) {
+            const float u = l_u[sl];
+            Elem<E>::store(a.uvals + row * K + sl, u);
+            Elem<E>::store(zrow + j, silu_f32(g) * u);
+        }
+    }
+    if (FUSED) {
+        __syncthreads();
+        constexpr int PER = 16 / (int)sizeof(E);
+        E* zout = a.zd + row * a.ldz;
+        for (int i = tid * PER; i < ldz; i += NT * PER)
+            *reinterpret_cast<u32x4_t*>(zout + i) = *reinterpret_cast<const u32x4_t*>(zrow + i);
+    }
+}
+
+// Dynamic LDS of topk_rows_kernel: two digit histograms, reused for the three slot lists and, in
+// the fused forward, the dense row.
+inline size_t topk_reg_dyn_lds(int K, int64_t ldz, size_t elem, bool fused) {
+    size_t lists = (size_t)3 * K * 4;
+    lists = (lists + 15) / 16 * 16;
+    if (fused) lists += (size_t)ldz * elem;
+    const size_t hists = (size_t)2 * kTopkBins * 4;
+    return lists > hists ? lists : hists;
 }
 
 inline size_t topk_lds_bytes(int F, int NT, int VEC) {
