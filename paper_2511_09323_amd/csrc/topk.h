@@ -295,12 +295,11 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     f32x4_t gv[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int j0 = c * CHUNK + tid * 4;
-        if (j0 + 3 < F) gv[c] = *reinterpret_cast<const f32x4_t*>(grow + j0);
-        else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) gv[c][e] = (j0 + e < F) ? grow[j0 + e] : 0.0f;
-        }
+        // ldg is a multiple of 4, so the aligned 16-byte block that holds channel j0 < F lies inside
+        // the row pitch; what it holds past F is masked out when the keys are made
+        // Threads past the end of the row re-read its last block instead of branching.
+        const int j0 = min(c * CHUNK + tid * 4, ((F + 3) & ~3) - 4);
+        gv[c] = *reinterpret_cast<const f32x4_t*>(grow + j0);
     }
     u32x2_t uraw[NCH];     // FUSED, E = bf16: four packed values
     f32x4_t uf[NCH];       // FUSED, E = float
@@ -308,18 +307,17 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         const E* urow = a.u + row * a.ldu;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const int j0 = c * CHUNK + tid * 4;
-            if (sizeof(E) == 2) {
-                uraw[c] = u32x2_t{0, 0};
-                if (j0 < a.ldu) uraw[c] = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const bf16_t*>(urow) + j0);
-            } else {
-                uf[c] = f32x4_t{0, 0, 0, 0};
-                if (j0 < a.ldu) uf[c] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(urow) + j0);
-            }
+            const int j0 = min(c * CHUNK + tid * 4, (int)a.ldu - 4);      // ldu is a multiple of 64
+            if (sizeof(E) == 2) uraw[c] = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const bf16_t*>(urow) + j0);
+            else uf[c] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(urow) + j0);
         }
     }
     for (int i = tid; i < 2 * kTopkBins; i += NT) (&hist[0][0])[i] = 0;
 
+    // Keys of channels past F: below 2^23, i.e. below the key of every finite value, so they are
+    // never selected and need no range check later; spread over the four lowest bins of the first
+    // digit so that their histogram updates do not pile up on one address.
+    const uint32_t pad_key = (uint32_t)(lane & 3) << 21;
     uint32_t key[NCH][4];
     int npos = 0;
 #pragma unroll
@@ -327,8 +325,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool in = c * CHUNK + tid * 4 + e < F;
-            key[c][e] = in ? float_key(gv[c][e]) : 0u;
-            npos += (in && (key[c][e] >> 31)) ? 1 : 0;
+            key[c][e] = in ? float_key(gv[c][e]) : pad_key;
+            npos += (int)(key[c][e] >> 31);
         }
     // ---- sign digit: keys with the top bit set are the non-negative values
     npos = (int)wave_sum((float)npos);                       // exact: counts are far below 2^24
@@ -354,8 +352,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const uint32_t k = key[c][e];
-                const bool in = c * CHUNK + tid * 4 + e < F;
-                if (in && (k >> pshift) == prefix) atomicAdd(&cur[(k >> shift) & (nbins - 1)], 1u);
+                if ((k >> pshift) == prefix) atomicAdd(&cur[(k >> shift) & (nbins - 1)], 1u);
             }
         __syncthreads();
         if (wave == 0) {
@@ -397,8 +394,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     }
     const uint32_t tau = prefix;
     const bool all_ties = cnt_eq == need;        // every key equal to tau is selected (the usual case)
-    // "above" test as one unsigned compare: k >= thr.  Padding keys are 0 and every real key of a
-    // finite value is at least 0x007FFFFF, so padding never passes and needs no range check.
+    // "above" test as one unsigned compare: k >= thr (padding keys lie below every finite key).
     const uint32_t thr = tau + ((all_ties || tau == 0xFFFFFFFFu) ? 0u : 1u);
 
     // ---- one ballot sweep: per-lane prefixes in registers, per-wave totals to LDS
