@@ -55,10 +55,12 @@ __device__ __forceinline__ void moc_bwd_pointwise(float g, float u, float dz, fl
 }
 
 // Order-preserving map float -> uint32: a > b  <=>  key(a) > key(b); -0.0 and +0.0 share a key.
+// Branch-free: flip all bits of negative values and the sign bit of the others; -0.0 lands on
+// 0x7FFFFFFF, one below the key of +0.0 and the image of no other value, and is bumped up.
 __device__ __forceinline__ uint32_t float_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0u;
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t k = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+    return k + (k == 0x7FFFFFFFu ? 1u : 0u);
 }
 __device__ __forceinline__ float key_float(uint32_t k) {
     uint32_t u = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             else uf[c] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(urow) + j0);
         }
     }
-    for (int i = tid; i < 2 * kTopkBins; i += NT) (&hist[0][0])[i] = 0;
+    for (int i = tid * 4; i < 2 * kTopkBins; i += NT * 4) *reinterpret_cast<u32x4_t*>(&hist[0][0] + i) = u32x4_t{0, 0, 0, 0};
 
     // Keys of channels past F: below 2^23, i.e. below the key of every finite value, so they are
     // never selected and need no range check later; spread over the four lowest bins of the first
@@ -321,13 +321,17 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     uint32_t key[NCH][4];
     int npos = 0;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c)
+    for (int c = 0; c < NCH; ++c) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = c * CHUNK + tid * 4 + e < F;
-            key[c][e] = in ? float_key(gv[c][e]) : pad_key;
-            npos += (int)(key[c][e] >> 31);
+        for (int e = 0; e < 4; ++e) key[c][e] = float_key(gv[c][e]);
+        if ((c + 1) * CHUNK > F) {                          // only the chunks that reach past the row (uniform)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c * CHUNK + tid * 4 + e >= F) key[c][e] = pad_key;
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) npos += (int)(key[c][e] >> 31);
+    }
     // ---- sign digit: keys with the top bit set are the non-negative values
     npos = (int)wave_sum((float)npos);                       // exact: counts are far below 2^24
     if (lane == 0) red[wave] = npos;
@@ -457,9 +461,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         }
     }
     // ---- slot lists and the dense row take over the histogram memory (dead since the last pass)
-    int* l_idx = reinterpret_cast<int*>(topk_dyn);                     // [K]
-    float* l_g = reinterpret_cast<float*>(topk_dyn) + K;               // [K]
-    float* l_u = l_g + K;                                              // [K]   (FUSED)
+    uint32_t* rec = reinterpret_cast<uint32_t*>(topk_dyn);            // [K] records {channel, key, up value}
     E* zrow = reinterpret_cast<E*>(topk_dyn + ((size_t)3 * K * 4 + 15) / 16 * 16);   // [ldz] (FUSED)
     const int ldz = FUSED ? (int)a.ldz : 0;
     if (FUSED) {
@@ -488,10 +490,10 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             for (int e = 0; e < 4; ++e) {
                 const uint32_t k = key[c][e];
                 if (k >= thr) {
-                    const int slot = min(gt_before, K - 1);
-                    l_idx[slot] = j0 + e;
-                    l_g[slot] = key_float(k);
-                    if (FUSED) l_u[slot] = uu[e];
+                    uint32_t* r = rec + 3 * min(gt_before, K - 1);
+                    r[0] = (uint32_t)(j0 + e);
+                    r[1] = k;
+                    if (FUSED) r[2] = __float_as_uint(uu[e]);
                     ++gt_before;
                 }
             }
@@ -502,10 +504,10 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                 const uint32_t k = key[c][e];
                 const bool isgt = k >= thr, iseq = k == tau;
                 if (isgt || (iseq && eq_before < need)) {
-                    const int slot = min(gt_before + min(eq_before, need), K - 1);
-                    l_idx[slot] = j0 + e;
-                    l_g[slot] = key_float(k);
-                    if (FUSED) l_u[slot] = uu[e];
+                    uint32_t* r = rec + 3 * min(gt_before + min(eq_before, need), K - 1);
+                    r[0] = (uint32_t)(j0 + e);
+                    r[1] = k;
+                    if (FUSED) r[2] = __float_as_uint(uu[e]);
                 }
                 gt_before += isgt ? 1 : 0;
                 eq_before += iseq ? 1 : 0;
@@ -515,13 +517,13 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     __syncthreads();
     // ---- write the compact outputs slot by slot (coalesced) and scatter z' into the dense row
     for (int sl = tid; sl < K; sl += NT) {
-        const int j = l_idx[sl];
-        const float g = l_g[sl];
+        const int j = (int)rec[3 * sl];
+        const float g = key_float(rec[3 * sl + 1]);
         a.idx[row * K + sl] = j;
         if (a.gsel_f32) a.gsel_f32[row * K + sl] = g;
         if (a.gvals) Elem<E>::store(a.gvals + row * K + sl, g);
         if (FUSED) {
-            const float u = l_u[sl];
+            const float u = __uint_as_float(rec[3 * sl + 2]);
             Elem<E>::store(a.uvals + row * K + sl, u);
             Elem<E>::store(zrow + j, silu_f32(g) * u);
         }
