@@ -101,7 +101,8 @@ moc_status moc_swiglu_bwd(const moc_shape* shape, const void* x, const void* wg,
 
 /* Row-wise Top-K alone (the mask definition of section "Mixture-of-Channels architecture"):
  * g[T, ldg] fp32 (ldg >= F elements) -> idx[T,K] ascending by channel and gsel[T,K] fp32, the gate
- * values there.  Needs no workspace. */
+ * values there.  Needs no workspace.  When ldg is a multiple of 4 and g is 16-byte aligned, the
+ * aligned 16-byte block that holds the last element of a row is read whole. */
 moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_t ldg,
                          int32_t* idx, float* gsel, void* hip_stream);
 
