@@ -376,10 +376,9 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
     // 256 threads per row keep up to 24 values per thread in registers; longer rows get 512 threads
-    const int topk_nt = env_int("MOC_TOPK_NT", D.ldF > 6144 ? 512 : 256);
-    if (gb == 0) s = topk_nt == 1024  ? run_topk<E, 1024, true>("topk_select_act", a, D.T, st)
-                     : topk_nt == 512 ? run_topk<E, 512, true>("topk_select_act", a, D.T, st)
-                                      : run_topk<E, 256, true>("topk_select_act", a, D.T, st);
+    // (1024 measured slower)
+    if (gb == 0) s = D.ldF > 6144 ? run_topk<E, 512, true>("topk_select_act", a, D.T, st)
+                                  : run_topk<E, 256, true>("topk_select_act", a, D.T, st);
     else s = run_group_select<E, true>("group_select_act", a, D.T, ga, gb, st);      // MoC_{a:b}
     if (s != MOC_OK) return s;
     return down_projection<E>(D, W.Zd, wd, y, st);
