@@ -517,7 +517,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     __syncthreads();
     // ---- write the compact outputs slot by slot (coalesced) and scatter z' into the dense row
     for (int sl = tid; sl < K; sl += NT) {
-        const int j = (int)rec[3 * sl];
+        const int j = min((int)rec[3 * sl], F - 1);       // the clamp only matters for non-finite input
         const float g = key_float(rec[3 * sl + 1]);
         a.idx[row * K + sl] = j;
         if (a.gsel_f32) a.gsel_f32[row * K + sl] = g;

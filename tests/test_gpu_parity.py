@@ -71,7 +71,8 @@ def _topk_case(g_np, K):
 def test_topk_bit_exact_random_and_adversarial():
     rng = np.random.default_rng(7)
     for T, F, K in [(5, 1, 1), (3, 7, 7), (4, 64, 1), (9, 333, 41), (16, 1376, 172), (8, 5461, 683),
-                    (4, 11008, 1376), (2, 32768, 4096), (3, 1023, 1000), (2, 2050, 3), (2, 8000, 5000), (3, 11264, 4096)]:
+                    (4, 11008, 1376), (2, 32768, 4096), (3, 1023, 1000), (2, 2050, 3), (2, 8000, 5000), (3, 11264, 4096),
+                    (2, 11008, 9000), (3, 6144, 6143), (2, 4100, 4100)]:
         say("[topk] random T=%d F=%d K=%d" % (T, F, K))
         _topk_case(rng.standard_normal((T, F)).astype(np.float32), K)
     say("[topk] ties, signed zeros, constant rows, negative rows")
