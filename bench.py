@@ -61,7 +61,7 @@ def gemm_flops(T, d, F, K):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards over tokens; see DESIGN.md); "
+        print("bench.py: this build measures one GPU only (the path shards over tokens and needs no second GPU to be measured); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
