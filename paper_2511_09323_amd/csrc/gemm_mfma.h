@@ -10,8 +10,8 @@
 // plain 16-byte reads; KM tiles are staged as [k][row] exactly as they lie in memory and fragments
 // come from two ds_read_b64_tr_b16 transposing reads (each gives a lane 4 consecutive k of one row).
 //
-// One 256-thread workgroup computes a BM x BN tile; its 2 x 2 wavefronts each own a
-// (BM/2) x (BN/2) sub-tile of 32x32 MFMA blocks.  k-slices of 32 are staged global -> registers
+// One workgroup of NWV wavefronts (4 or 8) computes a BM x BN tile; its 2 x (NWV/2) wavefronts each
+// own a (BM/2) x (BN/(NWV/2)) sub-tile of 32x32 MFMA blocks.  k-slices of 32 are staged global -> registers
 // -> LDS through three LDS stages: while slice t is multiplied, slice t+1 is already visible in
 // LDS, slice t+2 is being written and slices t+3, t+4 are in flight from global memory.  One barrier per
 // slice.  Fragment registers are double-buffered so LDS reads overlap the MFMAs of the previous
@@ -60,7 +60,7 @@ __device__ __forceinline__ int kc_lds_offset(int row, int ch) {
 template <int ROWS, bool KM> struct OperandTile {
     static constexpr int kPitch = KM ? (ROWS * 2 + 64) : (kKcSwizzle ? kMfmaBK * 2 : kMfmaBK * 2 + 16);   // bytes
     static constexpr int kBytes = KM ? kMfmaBK * kPitch : ROWS * kPitch;
-    static constexpr int kChunks = ROWS * kMfmaBK / 8 / 256;                    // 16-byte chunks per thread
+    static constexpr int kChunks64 = ROWS * kMfmaBK / 8 / 64;                   // 16-byte chunks per lane of one wavefront
 };
 
 template <int BM, int BN, bool AKM, bool BKM> struct MfmaCfg {
@@ -110,16 +110,19 @@ template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, 
     }
 };
 
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi>
-__global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int MINB = 1>
+__global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
     constexpr int BK = kMfmaBK;
-    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int NT = NWV * 64;
+    constexpr int WAVES_N = NWV / 2;                   // wavefronts form a 2 x (NWV/2) grid over the tile
+    constexpr int WM = BM / 2, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int LA = TA::kChunks, LB = TB::kChunks;
-    static_assert(LA >= 1 && LB >= 1, "tile too small for 256 threads");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must consist of 32x32 blocks");
+    constexpr int LA = TA::kChunks64 / NWV, LB = TB::kChunks64 / NWV;
+    static_assert(LA >= 1 && LB >= 1, "tile too small for this many threads");
     extern __shared__ __align__(16) unsigned char smem[];
     const int M = pr.M, N = pr.N;
 
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
     // ---- staging assignment.  KC: chunk c -> (row c / 4, k chunk c % 4); rows past the edge are
     //      clamped.  KM: chunk c -> (k row c / (ROWS/8), column chunk c % (ROWS/8)); columns past
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
     int b_off[LB], b_lds[LB], b_k[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        const int c = tid + i * 256;
+        const int c = tid + i * NT;
         if (!AKM) {
             const int row = c >> 2, ch = c & 3;
             a_off[i] = min(m0 + row, M - 1) * (int)pr.A.ld + ch * 8;
@@ -163,7 +166,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-        const int c = tid + i * 256;
+        const int c = tid + i * NT;
         if (!BKM) {
             const int row = c >> 2, ch = c & 3;
             b_off[i] = min(n0 + row, N - 1) * (int)pr.B.ld + ch * 8;
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(MfmaProblem pr, int
     //      epilogue functor whole row segments: 32 lanes x 4 columns = 128 consecutive columns.
     {
         constexpr int EPITCH = WN * 4 + 16;                       // bytes per staged row (fp32)
-        static_assert(4 * 32 * EPITCH <= Cfg::kLds, "epilogue staging must fit in the stage memory");
+        static_assert(NWV * 32 * EPITCH <= Cfg::kLds, "epilogue staging must fit in the stage memory");
         unsigned char* area = smem + wave * (32 * EPITCH);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -344,10 +347,10 @@ inline bool mfma_problem_ok(const MfmaProblem& p) {
     return ok && operand_ok(p.A, p.M, two) && operand_ok(p.B, p.N, two);
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int MINB = 1>
 inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
-    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi>;
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, MINB>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -356,7 +359,7 @@ inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hi
         attr_set = true;
     }
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
     return hipGetLastError();
 }
 

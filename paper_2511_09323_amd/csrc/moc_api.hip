@@ -147,7 +147,14 @@ moc_status check_shape(const moc_shape* s, bool decode) {
 template <int BM, int BN, bool AKM, bool BKM, class Epi>
 hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t st) {
     const bool tail = pr.Kc % kMfmaBK != 0 || pr.Kc2 % kMfmaBK != 0;
-    if (!tail) return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi>(pr, epi, st);
+    if (!tail) {
+        // 256x256 tiles with both operands k-contiguous (gate, up, dZ'): eight wavefronts (2 x 4) measured
+        // 5 % faster than four at the short contractions these products have, equal at long ones
+        if constexpr (BM == 256 && BN == 256 && !AKM && !BKM)
+            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi, 8>(pr, epi, st);
+        else
+            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi>(pr, epi, st);
+    }
     if constexpr (AKM != BKM) {
         const GemmOperand<bf16_t>& kc = AKM ? pr.B : pr.A;
         const int kmax = std::max(pr.Kc, pr.Kc2);
