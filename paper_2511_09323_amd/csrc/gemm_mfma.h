@@ -13,7 +13,7 @@
 // One workgroup of NWV wavefronts (4 or 8) computes a BM x BN tile; its 2 x (NWV/2) wavefronts each
 // own a (BM/2) x (BN/(NWV/2)) sub-tile of 32x32 MFMA blocks.  k-slices of 32 are staged global -> registers
 // -> LDS through three LDS stages: while slice t is multiplied, slice t+1 is already visible in
-// LDS, slice t+2 is being written and slices t+3, t+4 are in flight from global memory.  One barrier per
+// LDS, slice t+2 is being written and slices t+3 .. t+2+NSETS are in flight from global memory.  One barrier per
 // slice.  Fragment registers are double-buffered so LDS reads overlap the MFMAs of the previous
 // half-slice; sched_group_barrier pins that interleaving.
 //
@@ -110,8 +110,8 @@ template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, 
     }
 };
 
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int MINB = 1>
-__global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProb
     const int nk = nk0 + (pr.Kc2 + BK - 1) / BK;
     const int lda = (int)pr.A.ld, ldb = (int)pr.B.ld;
 
-    u32x4_t ga[2][LA], gb[2][LB];   // two slices in flight from global memory
+    u32x4_t ga[NSETS][LA], gb[NSETS][LB];   // NSETS slices in flight from global memory
     // global -> registers for k-slice kt (clamped to the last slice so the loop body has no branch)
     auto fetch = [&](int buf, int kt) {
         kt = min(kt, nk - 1);
@@ -250,13 +250,13 @@ __global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProb
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[buf][j], fm[buf][i], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: slices 0 and 1 into LDS, slices 2 and 3 into registers
+    // ---- prologue: slices 0 and 1 into LDS, slices 2 .. NSETS+1 into registers
     fetch(0, 0);
     fetch(1, 1);
     stash(0, 0);
     stash(1, 1);
-    fetch(0, 2);
-    fetch(1, 3);
+#pragma unroll
+    for (int i = 0; i < NSETS; ++i) fetch(i, 2 + i);
     __syncthreads();
     load_frags(0, 0, 0);
 
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProb
         load_frags(1, st_cur, 1);       // second half of slice kt
         stash(buf, st_fill);            // slice kt+2 -> LDS (its stage was last read in slice kt-1)
         mma(0);
-        fetch(buf, kt + 4);             // slice kt+4 -> registers
+        fetch(buf, kt + 2 + NSETS);     // slice kt+2+NSETS -> registers
         load_frags(0, st_next, 0);      // first half of slice kt+1 (visible since the last barrier)
         mma(1);
         // first half: the fragment reads go out with the first quarter of the MFMAs, the LDS writes
@@ -285,11 +285,16 @@ __global__ __launch_bounds__(NWV * 64, MINB) void gemm_bf16_mfma_kernel(MfmaProb
         st_fill = t;
     };
     int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
+    for (; kt + NSETS <= nk; kt += NSETS) {
         slice(std::integral_constant<int, 0>{}, kt);
         slice(std::integral_constant<int, 1>{}, kt + 1);
+        if constexpr (NSETS > 2) slice(std::integral_constant<int, 2>{}, kt + 2);
+        if constexpr (NSETS > 3) slice(std::integral_constant<int, 3>{}, kt + 3);
     }
-    if (kt < nk) slice(std::integral_constant<int, 0>{}, kt);
+    if (kt < nk) slice(std::integral_constant<int, 0>{}, kt++);
+    if (kt < nk) slice(std::integral_constant<int, 1>{}, kt++);
+    if constexpr (NSETS > 3)
+        if (kt < nk) slice(std::integral_constant<int, 2>{}, kt++);
 
     // ---- epilogue.  acc[i][j][4*ii + r] is C[m, n] with m = .. + lane % 32 and n = .. + 8*ii +
     //      4*(lane/32) + r: a lane owns 4 consecutive n of 32 different rows, which would make
@@ -347,10 +352,11 @@ inline bool mfma_problem_ok(const MfmaProblem& p) {
     return ok && operand_ok(p.A, p.M, two) && operand_ok(p.B, p.N, two);
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int MINB = 1>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
 inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st) {
+    static_assert(NSETS >= 2 && NSETS <= 4, "two to four slices in flight");
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
-    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, MINB>;
+    auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

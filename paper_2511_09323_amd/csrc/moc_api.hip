@@ -147,21 +147,17 @@ moc_status check_shape(const moc_shape* s, bool decode) {
 template <int BM, int BN, bool AKM, bool BKM, class Epi>
 hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t st) {
     const bool tail = pr.Kc % kMfmaBK != 0 || pr.Kc2 % kMfmaBK != 0;
-    if (!tail) {
-        // 256x256 tiles with both operands k-contiguous (gate, up, dZ'): eight wavefronts (2 x 4) measured
-        // 5 % faster than four at the short contractions these products have, equal at long ones
-        if constexpr (BM == 256 && BN == 256 && !AKM && !BKM)
-            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi, 8>(pr, epi, st);
-        else
-            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi>(pr, epi, st);
-    }
+    // Four wavefronts, three k-slices in flight from global memory.  Measured over the whole training step:
+    // three slices beat two by 1.3 %, four give nothing more; eight wavefronts (2 x 4) are faster in
+    // isolation at short contractions but 2.5 % slower over the step.
+    if (!tail) return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi, 4, 3>(pr, epi, st);
     if constexpr (AKM != BKM) {
         const GemmOperand<bf16_t>& kc = AKM ? pr.B : pr.A;
         const int kmax = std::max(pr.Kc, pr.Kc2);
         if (pr.kc_zero_padded && kc.ld >= round_up(kmax, kMfmaBK))
-            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 2, Epi>(pr, epi, st);
+            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 2, Epi, 4, 3>(pr, epi, st);
     }
-    return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 1, Epi>(pr, epi, st);
+    return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 1, Epi, 4, 3>(pr, epi, st);
 }
 
 // Runs C = A B^T (+ second segment) with the epilogue `epi`.  AKM / BKM state the operand layouts
