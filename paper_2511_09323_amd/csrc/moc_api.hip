@@ -168,10 +168,10 @@ moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, 
     Span span(name, st);
     if constexpr (std::is_same<E, bf16_t>::value) {
         if (!options().force_generic && mfma_problem_ok(pr)) {
-            // tile shape: fewest rounds of workgroups over the 256 CUs, weighted by tile area and a
-            // small efficiency penalty for the smaller shapes
+            // tile shape: fewest rounds of workgroups over the 256 CUs, weighted by tile area and the
+            // measured efficiency of the smaller shapes (they stage more LDS bytes per FLOP)
             struct Cand { int bm, bn; double penalty; };
-            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.06}, {128, 128, 1.3}};
+            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.15}, {128, 128, 1.6}};
             int best = 0;
             double best_cost = 0.0;
             for (int c = 0; c < 3; ++c) {
