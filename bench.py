@@ -54,6 +54,7 @@ def gemm_flops(T, d, F, K):
         "gemm_dwd": (ex, al),
         "gemm_dwg": (ex, al),
         "gemm_dwu": (ex, al),
+        "gemm_dw3": (3 * ex, 3 * al),                # dW_down, dW_gate, dW_up in one launch
         "gemm_dx": (2 * ex, 2 * al),
     }
 

@@ -110,8 +110,9 @@ template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, 
     }
 };
 
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
-__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
+// One output tile: workgroup-wide, `w` is the tile's index in launch order.
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
+__device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi, int w) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
@@ -129,7 +130,6 @@ __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr
     // ---- workgroup -> tile: contiguous tile ranges per XCD (workgroup w runs on XCD w % 8),
     //      tiles ordered in bands of 8 tile-rows so one XCD's L2 sees few distinct panels.
     const int nblk = tiles_m * tiles_n;
-    const int w = blockIdx.x;
     const int xcd = w & 7, local = w >> 3;
     const int logical = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
     constexpr int GROUP = 8;
@@ -336,6 +336,26 @@ __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr
     }
 }
 
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
+    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(pr, tiles_m, tiles_n, epi, blockIdx.x);
+}
+
+// NB independent problems of one shape and layout in one launch (the three weight-gradient products
+// of the backward): workgroup w works on problem w / tiles, tile w % tiles.  Small problems fill the
+// chip together where each alone would not, and two launches are saved.
+template <class Epi, int NB> struct MfmaBatch {
+    MfmaProblem pr[NB];
+    Epi epi[NB];
+};
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatch<Epi, NB> b, int tiles_m, int tiles_n) {
+    const int nblk = tiles_m * tiles_n;
+    const int z = blockIdx.x / nblk;
+    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], blockIdx.x - z * nblk);
+}
+
 // Host-side check of the kernel's layout assumptions (the caller vouches for the zero padding of
 // k-contiguous operands past a contraction length that is not a multiple of 8).
 inline bool mfma_problem_ok(const MfmaProblem& p) {
@@ -366,6 +386,22 @@ inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hi
     }
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_batch_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(NB * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

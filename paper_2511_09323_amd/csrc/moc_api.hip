@@ -194,6 +194,46 @@ moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, 
     return MOC_OK;
 }
 
+// Three independent products of one shape (both operands k-major, plain stores) in one launch when
+// the MFMA kernel takes them; otherwise one run_gemm each.  Same tile choice as run_gemm, over the
+// tiles of all three.
+template <class E>
+moc_status run_gemm_batch3(const char* name, const char* const names[3], const GemmProblem<E> pr[3], const EpiStore<E> epi[3],
+                           hipStream_t st) {
+    if constexpr (std::is_same<E, bf16_t>::value) {
+        const bool same = pr[0].M == pr[1].M && pr[0].M == pr[2].M && pr[0].N == pr[1].N && pr[0].N == pr[2].N &&
+                          pr[0].Kc == pr[1].Kc && pr[0].Kc == pr[2].Kc && pr[0].Kc % kMfmaBK == 0 && pr[0].Kc2 == 0 &&
+                          pr[1].Kc2 == 0 && pr[2].Kc2 == 0;
+        if (same && !options().force_generic && mfma_problem_ok(pr[0]) && mfma_problem_ok(pr[1]) && mfma_problem_ok(pr[2])) {
+            struct Cand { int bm, bn; double penalty; };
+            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.15}, {128, 128, 1.6}};
+            int best = 0;
+            double best_cost = 0.0;
+            for (int c = 0; c < 3; ++c) {
+                const int64_t tiles = 3 * (int64_t)((pr[0].M + cands[c].bm - 1) / cands[c].bm) * ((pr[0].N + cands[c].bn - 1) / cands[c].bn);
+                const double cost = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn * cands[c].penalty;
+                if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
+            }
+            if (options().tile == 256) best = 0;
+            if (options().tile == 192) best = 1;
+            if (options().tile == 128) best = 2;
+            MfmaBatch<EpiStore<E>, 3> b;
+            for (int i = 0; i < 3; ++i) { b.pr[i] = pr[i]; b.epi[i] = epi[i]; }
+            Span span(name, st);
+            hipError_t e = best == 0   ? launch_gemm_bf16_mfma_batch<256, 256, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st)
+                           : best == 1 ? launch_gemm_bf16_mfma_batch<256, 192, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st)
+                                       : launch_gemm_bf16_mfma_batch<128, 128, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st);
+            if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+            return MOC_OK;
+        }
+    }
+    for (int i = 0; i < 3; ++i) {
+        moc_status s = run_gemm<E, true, true>(names[i], pr[i], epi[i], st);
+        if (s != MOC_OK) return s;
+    }
+    return MOC_OK;
+}
+
 // LDS-resident Top-K: any row length up to the LDS capacity, any alignment.
 template <class E, int NT, int VEC, bool FUSED>
 moc_status run_topk_lds(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
@@ -424,12 +464,14 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     }
     // dW_down = Z'^T dD (bp-1); dW_gate = X^T dG, dW_up = X^T dU (bp-4): contractions over tokens,
     // both operands read k-major (token index leading)
-    GemmProblem<E> pwd{km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0, false};
-    if ((s = run_gemm<E, true, true>("gemm_dwd", pwd, EpiStore<E>{dwd, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    GemmProblem<E> pwg{km_operand<E>(W.dGd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false};
-    if ((s = run_gemm<E, true, true>("gemm_dwg", pwg, EpiStore<E>{dwg, D.d, D.d, 0}, st)) != MOC_OK) return s;
-    GemmProblem<E> pwu{km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false};
-    if ((s = run_gemm<E, true, true>("gemm_dwu", pwu, EpiStore<E>{dwu, D.d, D.d, 0}, st)) != MOC_OK) return s;
+    // (one launch for the three of them)
+    const GemmProblem<E> pw[3] = {
+        {km_operand<E>(W.Zd, D.ldF, D.ldF), km_operand<E>(dy, D.d, D.d), D.F, D.d, D.T, 0, false},
+        {km_operand<E>(W.dGd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false},
+        {km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false}};
+    const EpiStore<E> ew[3] = {{dwd, D.d, D.d, 0}, {dwg, D.d, D.d, 0}, {dwu, D.d, D.d, 0}};
+    static const char* const wnames[3] = {"gemm_dwd", "gemm_dwg", "gemm_dwu"};
+    if ((s = run_gemm_batch3<E>("gemm_dw3", wnames, pw, ew, st)) != MOC_OK) return s;
     // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
     GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F, true};
     return run_gemm<E, false, true>("gemm_dx", px, EpiStore<E>{dx, D.d, D.d, 0}, st);
