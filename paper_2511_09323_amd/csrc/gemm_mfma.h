@@ -356,6 +356,18 @@ __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatc
     gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], blockIdx.x - z * nblk);
 }
 
+// Two independent problems of one shape and layout with different epilogues in one launch (gate and
+// up projection of the forward): the first tiles_m * tiles_n workgroups take the first problem.
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class EpiA, class EpiB, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_pair_kernel(MfmaProblem pa, EpiA ea, MfmaProblem pb, EpiB eb,
+                                                                        int tiles_m, int tiles_n) {
+    const int nblk = tiles_m * tiles_n;
+    if ((int)blockIdx.x < nblk)
+        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiA, NWV, NSETS>(pa, tiles_m, tiles_n, ea, blockIdx.x);
+    else
+        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiB, NWV, NSETS>(pb, tiles_m, tiles_n, eb, blockIdx.x - nblk);
+}
+
 // Host-side check of the kernel's layout assumptions (the caller vouches for the zero padding of
 // k-contiguous operands past a contraction length that is not a multiple of 8).
 inline bool mfma_problem_ok(const MfmaProblem& p) {
@@ -402,6 +414,23 @@ inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipSt
     }
     const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(NB * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class EpiA, class EpiB, int NWV = 4, int NSETS = 2>
+inline hipError_t launch_gemm_bf16_mfma_pair(const MfmaProblem& pa, const EpiA& ea, const MfmaProblem& pb, const EpiB& eb,
+                                             hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_pair_kernel<BM, BN, AKM, BKM, TAILMODE, EpiA, EpiB, NWV, NSETS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (pa.M + BM - 1) / BM, tiles_n = (pa.N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(2 * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, pa, ea, pb, eb, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

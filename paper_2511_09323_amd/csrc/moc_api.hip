@@ -234,6 +234,48 @@ moc_status run_gemm_batch3(const char* name, const char* const names[3], const G
     return MOC_OK;
 }
 
+// Two independent products of one shape (both operands k-contiguous, contraction a multiple of 32)
+// with different epilogues in one launch when the MFMA kernel takes them; otherwise one run_gemm each.
+template <class E, class EpiA, class EpiB>
+moc_status run_gemm_pair(const char* name, const char* name_a, const char* name_b, const GemmProblem<E>& pa, const EpiA& ea,
+                         const GemmProblem<E>& pb, const EpiB& eb, hipStream_t st) {
+    if constexpr (std::is_same<E, bf16_t>::value) {
+        const bool same = pa.M == pb.M && pa.N == pb.N && pa.Kc == pb.Kc && pa.Kc % kMfmaBK == 0 && pa.Kc2 == 0 && pb.Kc2 == 0;
+        if (same && !options().force_generic && mfma_problem_ok(pa) && mfma_problem_ok(pb)) {
+            struct Cand { int bm, bn; double penalty; };
+            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.15}, {128, 128, 1.6}};
+            int best = 0;
+            double best_cost = 0.0, best_single = 0.0;
+            for (int c = 0; c < 3; ++c) {
+                const int64_t tiles = (int64_t)((pa.M + cands[c].bm - 1) / cands[c].bm) * ((pa.N + cands[c].bn - 1) / cands[c].bn);
+                const double unit = (double)cands[c].bm * cands[c].bn * cands[c].penalty;
+                const double cost = (double)((2 * tiles + 255) / 256) * unit;
+                const double single = (double)((tiles + 255) / 256) * unit;
+                if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
+                if (c == 0 || single < best_single) best_single = single;
+            }
+            if (options().tile == 256) best = 0;
+            if (options().tile == 192) best = 1;
+            if (options().tile == 128) best = 2;
+            // worth one launch only when the two together need fewer rounds of workgroups than apart
+            if (!(best_cost < 2.0 * best_single)) {
+                moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st);
+                if (s != MOC_OK) return s;
+                return run_gemm<E, false, false>(name_b, pb, eb, st);
+            }
+            Span span(name, st);
+            hipError_t e = best == 0   ? launch_gemm_bf16_mfma_pair<256, 256, false, false, 0, EpiA, EpiB, 4, 3>(pa, ea, pb, eb, st)
+                           : best == 1 ? launch_gemm_bf16_mfma_pair<256, 192, false, false, 0, EpiA, EpiB, 4, 3>(pa, ea, pb, eb, st)
+                                       : launch_gemm_bf16_mfma_pair<128, 128, false, false, 0, EpiA, EpiB, 4, 3>(pa, ea, pb, eb, st);
+            if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+            return MOC_OK;
+        }
+    }
+    moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st);
+    if (s != MOC_OK) return s;
+    return run_gemm<E, false, false>(name_b, pb, eb, st);
+}
+
 // LDS-resident Top-K: any row length up to the LDS capacity, any alignment.
 template <class E, int NT, int VEC, bool FUSED>
 moc_status run_topk_lds(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
@@ -411,11 +453,12 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     FwdWs<E> W(ws, D, false);
     moc_status s;
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
+    // and U = X W_up (Eq. MoC-1): one launch for both when possible
     GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0, false};
-    if ((s = run_gemm<E, false, false>("gemm_gate", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
-    // U = X W_up (Eq. MoC-1)
     GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0, false};
-    if ((s = run_gemm<E, false, false>("gemm_up", pu, EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
+    if ((s = run_gemm_pair<E>("gemm_gate_up", "gemm_gate", "gemm_up", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, pu,
+                              EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK)
+        return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
     // 256 threads per row keep up to 24 values per thread in registers; longer rows get 512 threads
