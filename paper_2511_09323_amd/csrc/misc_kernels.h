@@ -98,30 +98,104 @@ __global__ __launch_bounds__(256) void bwd_expand_kernel(const int32_t* __restri
     }
 }
 
+// 16 bytes of E as floats and back.
+template <class E> struct Vec16;
+template <> struct Vec16<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(u32x4_t t, float* v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(t[i]);
+    }
+    static __device__ __forceinline__ u32x4_t pack(const float* v) {
+        return u32x4_t{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+    }
+};
+template <> struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(u32x4_t t, float* v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(t[i] << 16);
+            v[2 * i + 1] = __uint_as_float(t[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ u32x4_t pack(const float* v) {
+        return u32x4_t{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+    }
+};
+
 // RMSNorm of one row per workgroup: out = x / sqrt(mean(x^2) + eps) * gain.
-template <class E>
+// VEC: rows are read once with 16-byte loads and kept in registers (needs d a multiple of the
+// 16-byte element count, d <= 256 * NV elements per 16 bytes, and 16-byte aligned pointers);
+// otherwise element by element, reading the row twice.
+template <class E, bool VEC, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const E* __restrict__ h, const E* __restrict__ gain, float eps,
                                                       int d, E* __restrict__ out) {
     __shared__ float red[4];
     const int64_t t = blockIdx.x;
     const E* x = h + t * d;
     float ss = 0.0f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = Elem<E>::load(x + i);
-        ss += v * v;
+    constexpr int CN = Vec16<E>::N;
+    u32x4_t raw[NV];
+    if (VEC) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int i = (u * 256 + threadIdx.x) * CN;
+            raw[u] = u32x4_t{0, 0, 0, 0};
+            if (i < d) raw[u] = *reinterpret_cast<const u32x4_t*>(x + i);
+            float v[CN];
+            Vec16<E>::unpack(raw[u], v);
+#pragma unroll
+            for (int e = 0; e < CN; ++e) ss = fmaf(v[e], v[e], ss);
+        }
+    } else {
+        for (int i = threadIdx.x; i < d; i += 256) {
+            float v = Elem<E>::load(x + i);
+            ss += v * v;
+        }
     }
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float tot = red[0] + red[1] + red[2] + red[3];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256)
-        Elem<E>::store(out + t * d + i, Elem<E>::load(x + i) * inv * Elem<E>::load(gain + i));
+    if (VEC) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int i = (u * 256 + threadIdx.x) * CN;
+            if (i < d) {
+                float v[CN], g[CN];
+                Vec16<E>::unpack(raw[u], v);
+                Vec16<E>::unpack(*reinterpret_cast<const u32x4_t*>(gain + i), g);
+#pragma unroll
+                for (int e = 0; e < CN; ++e) v[e] = v[e] * inv * g[e];
+                *reinterpret_cast<u32x4_t*>(out + t * d + i) = Vec16<E>::pack(v);
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < d; i += 256)
+            Elem<E>::store(out + t * d + i, Elem<E>::load(x + i) * inv * Elem<E>::load(gain + i));
+    }
 }
 
-template <class E> __global__ void residual_add_kernel(E* __restrict__ h, const E* __restrict__ y, int64_t n) {
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        Elem<E>::store(h + i, Elem<E>::load(h + i) + Elem<E>::load(y + i));
+// h <- h + y, element-wise.  VEC: 16 bytes per lane and step (n a multiple of the 16-byte element
+// count, 16-byte aligned pointers).
+template <class E, bool VEC> __global__ void residual_add_kernel(E* __restrict__ h, const E* __restrict__ y, int64_t n) {
+    if (VEC) {
+        constexpr int CN = Vec16<E>::N;
+        const int64_t nv = n / CN;
+        for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < nv; i += (int64_t)gridDim.x * blockDim.x) {
+            float a[CN], b[CN];
+            Vec16<E>::unpack(*reinterpret_cast<const u32x4_t*>(h + i * CN), a);
+            Vec16<E>::unpack(*reinterpret_cast<const u32x4_t*>(y + i * CN), b);
+#pragma unroll
+            for (int e = 0; e < CN; ++e) a[e] += b[e];
+            *reinterpret_cast<u32x4_t*>(h + i * CN) = Vec16<E>::pack(a);
+        }
+    } else {
+        for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+            Elem<E>::store(h + i, Elem<E>::load(h + i) + Elem<E>::load(y + i));
+    }
 }
 
 }  // namespace moc

@@ -889,10 +889,21 @@ moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const
     CHECK_PTR(h); CHECK_PTR(gain); CHECK_PTR(out);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Span span("rmsnorm", st);
-    if (dtype == MOC_BF16)
-        hipLaunchKernelGGL((rmsnorm_kernel<bf16_t>), dim3(T), dim3(256), 0, st, (const bf16_t*)h, (const bf16_t*)gain, eps, d, (bf16_t*)out);
-    else
-        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(T), dim3(256), 0, st, (const float*)h, (const float*)gain, eps, d, (float*)out);
+    if (dtype == MOC_BF16) {
+        const bf16_t *hp = (const bf16_t*)h, *gp = (const bf16_t*)gain;
+        bf16_t* op = (bf16_t*)out;
+        if (d % 8 == 0 && d <= 256 * 8 * 2)
+            hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, true, 2>), dim3(T), dim3(256), 0, st, hp, gp, eps, d, op);
+        else
+            hipLaunchKernelGGL((rmsnorm_kernel<bf16_t, false, 1>), dim3(T), dim3(256), 0, st, hp, gp, eps, d, op);
+    } else {
+        const float *hp = (const float*)h, *gp = (const float*)gain;
+        float* op = (float*)out;
+        if (d % 4 == 0 && d <= 256 * 4 * 4)
+            hipLaunchKernelGGL((rmsnorm_kernel<float, true, 4>), dim3(T), dim3(256), 0, st, hp, gp, eps, d, op);
+        else
+            hipLaunchKernelGGL((rmsnorm_kernel<float, false, 1>), dim3(T), dim3(256), 0, st, hp, gp, eps, d, op);
+    }
     HIP_TRY(hipGetLastError());
     return MOC_OK;
 }
@@ -904,11 +915,19 @@ moc_status moc_residual_add(int32_t T, int32_t d, int32_t dtype, void* h_inout, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Span span("residual_add", st);
     const int64_t n = (int64_t)T * d;
-    const unsigned grid = (unsigned)std::min<int64_t>((n + 255) / 256, 65536);
-    if (dtype == MOC_BF16)
-        hipLaunchKernelGGL((residual_add_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, (bf16_t*)h_inout, (const bf16_t*)y, n);
-    else
-        hipLaunchKernelGGL((residual_add_kernel<float>), dim3(grid), dim3(256), 0, st, (float*)h_inout, (const float*)y, n);
+    if (dtype == MOC_BF16) {
+        const bool vec = n % 8 == 0;
+        const int64_t work = vec ? n / 8 : n;
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((work + 255) / 256, 16384));
+        if (vec) hipLaunchKernelGGL((residual_add_kernel<bf16_t, true>), dim3(grid), dim3(256), 0, st, (bf16_t*)h_inout, (const bf16_t*)y, n);
+        else hipLaunchKernelGGL((residual_add_kernel<bf16_t, false>), dim3(grid), dim3(256), 0, st, (bf16_t*)h_inout, (const bf16_t*)y, n);
+    } else {
+        const bool vec = n % 4 == 0;
+        const int64_t work = vec ? n / 4 : n;
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((work + 255) / 256, 16384));
+        if (vec) hipLaunchKernelGGL((residual_add_kernel<float, true>), dim3(grid), dim3(256), 0, st, (float*)h_inout, (const float*)y, n);
+        else hipLaunchKernelGGL((residual_add_kernel<float, false>), dim3(grid), dim3(256), 0, st, (float*)h_inout, (const float*)y, n);
+    }
     HIP_TRY(hipGetLastError());
     return MOC_OK;
 }

@@ -245,9 +245,9 @@ def test_decode_small_shapes(B, d, F, K, dtype):
 
 
 # ------------------------------------------------------ RMSNorm, residual and the stack
+@pytest.mark.parametrize("T,d", [(37, 200), (5, 203), (3, 4096), (2, 8192), (1, 1)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_rmsnorm_and_residual(dtype):
-    T, d = 37, 200
+def test_rmsnorm_and_residual(dtype, T, d):
     h = inputs.normal((T, d), 950, 1.0, dtype)
     gain = inputs.normal((d,), 951, 1.0, dtype)
     yv = inputs.normal((T, d), 952, 1.0, dtype)
