@@ -110,9 +110,17 @@ template <int R, int N, int RA, int RB, int NR, int WA, int WB, int NW, int VA, 
     }
 };
 
-// One output tile: workgroup-wide, `w` is the tile's index in launch order.
+// Workgroup g of `total` runs on XCD g % 8.  Gives every XCD a contiguous range of the logical work
+// items 0 .. total-1, so that neighbouring items (tiles that share operand panels) meet in one L2.
+__device__ __forceinline__ int xcd_contiguous_index(int g, int total) {
+    const int xcd = g & 7, local = g >> 3;
+    return xcd * (total >> 3) + min(xcd, total & 7) + local;
+}
+
+// One output tile, workgroup-wide; `logical` is the tile's position in the band order described below.
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
-__device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi, int w) {
+__device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi,
+                                                    int logical) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
@@ -127,11 +135,8 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
     extern __shared__ __align__(16) unsigned char smem[];
     const int M = pr.M, N = pr.N;
 
-    // ---- workgroup -> tile: contiguous tile ranges per XCD (workgroup w runs on XCD w % 8),
-    //      tiles ordered in bands of 8 tile-rows so one XCD's L2 sees few distinct panels.
-    const int nblk = tiles_m * tiles_n;
-    const int xcd = w & 7, local = w >> 3;
-    const int logical = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+    // ---- tile order: bands of 8 tile-rows, column by column inside a band, so that a contiguous
+    //      range of tiles (one XCD's share) touches few distinct operand panels.
     constexpr int GROUP = 8;
     const int band = logical / (GROUP * tiles_n);
     const int first_m = band * GROUP;
@@ -338,12 +343,13 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
 
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
-    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(pr, tiles_m, tiles_n, epi, blockIdx.x);
+    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(pr, tiles_m, tiles_n, epi,
+                                                                     xcd_contiguous_index(blockIdx.x, tiles_m * tiles_n));
 }
 
 // NB independent problems of one shape and layout in one launch (the three weight-gradient products
-// of the backward): workgroup w works on problem w / tiles, tile w % tiles.  Small problems fill the
-// chip together where each alone would not, and two launches are saved.
+// of the backward): the work items are the tiles of all problems, problem after problem.  Small
+// problems fill the chip together where each alone would not, and two launches are saved.
 template <class Epi, int NB> struct MfmaBatch {
     MfmaProblem pr[NB];
     Epi epi[NB];
@@ -352,20 +358,22 @@ template <class Epi, int NB> struct MfmaBatch {
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatch<Epi, NB> b, int tiles_m, int tiles_n) {
     const int nblk = tiles_m * tiles_n;
-    const int z = blockIdx.x / nblk;
-    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], blockIdx.x - z * nblk);
+    const int item = xcd_contiguous_index(blockIdx.x, NB * nblk);
+    const int z = item / nblk;
+    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], item - z * nblk);
 }
 
 // Two independent problems of one shape and layout with different epilogues in one launch (gate and
-// up projection of the forward): the first tiles_m * tiles_n workgroups take the first problem.
+// up projection of the forward): the work items are the tiles of the first problem, then of the second.
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class EpiA, class EpiB, int NWV = 4, int NSETS = 2>
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_pair_kernel(MfmaProblem pa, EpiA ea, MfmaProblem pb, EpiB eb,
                                                                         int tiles_m, int tiles_n) {
     const int nblk = tiles_m * tiles_n;
-    if ((int)blockIdx.x < nblk)
-        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiA, NWV, NSETS>(pa, tiles_m, tiles_n, ea, blockIdx.x);
+    const int item = xcd_contiguous_index(blockIdx.x, 2 * nblk);
+    if (item < nblk)
+        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiA, NWV, NSETS>(pa, tiles_m, tiles_n, ea, item);
     else
-        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiB, NWV, NSETS>(pb, tiles_m, tiles_n, eb, blockIdx.x - nblk);
+        gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, EpiB, NWV, NSETS>(pb, tiles_m, tiles_n, eb, item - nblk);
 }
 
 // Host-side check of the kernel's layout assumptions (the caller vouches for the zero padding of
