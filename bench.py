@@ -130,6 +130,12 @@ def main():
     moc.timing_enable(False)
     moc.timing_reset()
     flops = gemm_flops(T, d, F, K)
+    ldF = (F + 63) // 64 * 64
+    # algorithmic HBM bytes per launch of the two streaming kernels (bf16 activations):
+    #   Top-K + SiLU.U: reads G fp32 and U, writes the dense Z' row and the stored set (idx, gvals, uvals);
+    #   pointwise + expansion: reads the stored set and the dense dZ' row, writes Z', dG, dU rows.
+    hbm_bytes = {"topk_select_act": T * (4 * F + 2 * F + 2 * ldF + K * 8),
+                 "bwd_pointwise_expand": T * (K * 8 + 2 * ldF + 3 * 2 * ldF)}
     kernels = []
     for name, (ms, n) in sorted(timing.items(), key=lambda kv: -kv[1][0]):
         avg_ms = ms / max(n, 1)
@@ -139,6 +145,9 @@ def main():
             row["executed_tflops"] = round(ex / (avg_ms * 1e-3) / 1e12, 2)
             row["algorithmic_tflops"] = round(al / (avg_ms * 1e-3) / 1e12, 2)
             row["frac_executed"] = round(row["executed_tflops"] / PEAK_BF16_TFLOPS, 4)
+        if name in hbm_bytes:
+            row["algorithmic_GBs"] = round(hbm_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
+            row["frac_hbm_peak"] = round(row["algorithmic_GBs"] / PEAK_HBM_GBS, 4)
         kernels.append(row)
     # roofline entry: the gate GEMM, the one contraction whose algorithmic FLOPs (2 d F per token)
     # equal the executed ones.  HBM traffic per launch comes from the committed rocprofv3 counter
