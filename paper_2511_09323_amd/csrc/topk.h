@@ -268,8 +268,8 @@ __global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
 
 // ---------------------------------------------------------------- register-resident variant
 // Row of up to NCH * NT * 4 channels; thread t holds channels c*NT*4 + t*4 .. +3 of every chunk c.
-// Per digit pass there are two barriers: after the histogram atomics, and after wave 0 has scanned
-// the bins (meanwhile the other waves clear the histogram of the next pass).  Channels are ranked
+// Per digit pass there are three barriers: after the histogram atomics, inside the workgroup-wide
+// scan of the bins, and after the crossing bin has been published.  Channels are ranked
 // with one ballot sweep whose per-lane prefixes stay in registers.  When all keys equal to the
 // threshold are selected (the usual case) a single ">= threshold" predicate is ranked; ties that
 // straddle the cut take the general path with a second predicate.  Selected channels are staged
@@ -359,36 +359,55 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                 if ((k >> pshift) == prefix) atomicAdd(&cur[(k >> shift) & (nbins - 1)], 1u);
             }
         __syncthreads();
-        if (wave == 0) {
-            // lane l owns bins nbins-1 - l*per .. nbins-1 - l*per - (per-1), i.e. descending order
-            const int per = nbins / 64;
+        {
+            // Suffix scan over all kTopkBins counters by the whole workgroup (a 10-bit pass leaves the
+            // upper half at zero): thread t owns the BPT bins below kTopkBins - BPT t, so thread order
+            // is descending bin order; the thread whose range crosses `need` publishes the result.
+            constexpr int BPT = kTopkBins / NT;
+            static_assert(BPT == 2 || BPT == 4 || BPT == 8, "bins per thread");
+            const int base = kTopkBins - BPT * (tid + 1);
+            uint32_t hv[BPT];
+            if (BPT == 2) {
+                const u32x2_t t2 = *reinterpret_cast<const u32x2_t*>(cur + base);
+                hv[0] = t2[0]; hv[1] = t2[1];
+            } else {
+#pragma unroll
+                for (int q = 0; q < BPT; q += 4) {
+                    const u32x4_t t4 = *reinterpret_cast<const u32x4_t*>(cur + base + q);
+                    hv[q] = t4[0]; hv[q + 1] = t4[1]; hv[q + 2] = t4[2]; hv[q + 3] = t4[3];
+                }
+            }
             int local = 0;
-            for (int q = 0; q < per; ++q) local += (int)cur[nbins - 1 - (lane * per + q)];
+#pragma unroll
+            for (int q = 0; q < BPT; ++q) local += (int)hv[q];
             int inc = local;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const int t = __shfl_up(inc, o, 64);
                 if (lane >= o) inc += t;
             }
+            if (lane == 63) red[wave] = inc;
+            __syncthreads();
+            int before = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) before += (w < wave) ? red[w] : 0;
+            inc += before;
             const int above = inc - local;
             if (above < need && inc >= need) {               // the crossing bin is one of mine
-                int run = above;
-                for (int q = 0; q < per; ++q) {
-                    const int b = nbins - 1 - (lane * per + q);
-                    const int h = (int)cur[b];
-                    if (run + h >= need) {
-                        sh_prefix = (prefix << nbits) | (uint32_t)b;
-                        sh_need = need - run;
-                        sh_cnt = h;
-                        break;
-                    }
+                int run = above, fb = -1, fneed = 0, fh = 0;
+#pragma unroll
+                for (int q = BPT - 1; q >= 0; --q) {         // descending bins
+                    const int h = (int)hv[q];
+                    if (fb < 0 && run + h >= need) { fb = base + q; fneed = need - run; fh = h; }
                     run += h;
                 }
+                sh_prefix = (prefix << nbits) | (uint32_t)fb;
+                sh_need = fneed;
+                sh_cnt = fh;
             }
-        } else if (pass < 2) {
-            uint32_t* nxt = hist[(pass + 1) & 1];
-            if (pass == 1) {                                  // buffer 0 was used by pass 0: clear it again
-                for (int i = tid - 64; i < kTopkBins; i += NT - 64) nxt[i] = 0;
+            if (pass == 1) {                                  // buffer 0 was used by pass 0: clear it for pass 2
+                uint32_t* nxt = hist[0];
+                for (int i = tid * 4; i < kTopkBins; i += NT * 4) *reinterpret_cast<u32x4_t*>(nxt + i) = u32x4_t{0, 0, 0, 0};
             }
         }
         __syncthreads();
