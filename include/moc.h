@@ -29,6 +29,11 @@
  *  - Errors: a negative moc_status is returned and moc_last_error() describes it (thread-local
  *    text).  Argument errors are found before anything is launched and leave outputs untouched.
  *  - Limits: 1 <= K <= F <= 32768, T >= 1 (T <= 16 for decode), d >= 1; MOC_BF16 needs d % 8 == 0.
+ *  - Environment variables for testing and tuning (none is needed in normal use):
+ *    MOC_FORCE_GENERIC=1 (read once) sends every GEMM to the generic fp32-FMA kernel and decode to
+ *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 (read once) forces an MFMA tile shape;
+ *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n (read at every call) switch off, or set the
+ *    workgroup count of, the single-launch grouped decode kernel.
  */
 #ifndef MOC_H
 #define MOC_H
