@@ -58,6 +58,21 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
     constexpr int CN = Chunk<E>::N;
     extern __shared__ __align__(16) unsigned char dec_smem[];
     E* xs = reinterpret_cast<E*>(dec_smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nwave = gridDim.x * 4;
+    constexpr int UN = 8;      // 16-byte chunks of a row per lane: rows of up to 64 * CN * UN elements in one go
+    const bool whole_rows = d <= 64 * CN * UN;
+    u32x4_t cur[UN], nxt[UN];
+    auto fetch = [&](u32x4_t (&r)[UN], int j) {
+        const E* wrow = wg + (int64_t)j * d;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = (u * 64 + lane) * CN;
+            r[u] = u32x4_t{0, 0, 0, 0};
+            if (k < d) r[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + k));
+        }
+    };
+    if (whole_rows && wave < F) fetch(cur, wave);          // in flight while x is staged
     for (int i = threadIdx.x * CN; i < BT * d; i += 256 * CN) {
         int b = i / d;
         u32x4_t v = {0, 0, 0, 0};
@@ -65,9 +80,35 @@ __global__ __launch_bounds__(256) void decode_gate_kernel(const E* __restrict__ 
         *reinterpret_cast<u32x4_t*>(xs + i) = v;
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6), nwave = gridDim.x * 4;
-    constexpr int UN = 8;      // 16-byte chunks of the row in flight per lane
+    if (whole_rows) {
+        // whole row in registers; the next row's loads are issued before this row is reduced
+        for (int j = wave; j < F; j += nwave) {
+            const bool more = j + nwave < F;
+            if (more) fetch(nxt, j + nwave);
+            float acc[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int k = (u * 64 + lane) * CN;
+                if (k < d) {
+#pragma unroll
+                    for (int b = 0; b < BT; ++b)
+                        acc[b] = Chunk<E>::dot(cur[u], *reinterpret_cast<const u32x4_t*>(xs + b * d + k), acc[b]);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float s = wave_sum(acc[b]);
+                if (lane == 0 && b < B) g[(int64_t)b * ldg + j] = s;
+            }
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < UN; ++u) cur[u] = nxt[u];
+            }
+        }
+        return;
+    }
     for (int j = wave; j < F; j += nwave) {
         const E* wrow = wg + (int64_t)j * d;
         float acc[BT];
