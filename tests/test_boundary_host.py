@@ -113,3 +113,11 @@ def test_python_binding_refuses_cpu_tensors(lib):
     w = torch.zeros(128, 64)
     with pytest.raises(B.MocError):
         B.moc_ffn_fwd(x, w, w, w, 16, ws=torch.zeros(1 << 20, dtype=torch.uint8))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
