@@ -292,3 +292,49 @@ def test_cfg4_stack_teacher_forced_layers():
         P.assert_close("y", P.to_np(y[sel]), D, P.TOL["bf16"])
         P.assert_close("h", P.to_np(h[sel]), O.residual_add(h_in, P.to_np(y[sel])), 1e-2)
         del Wd_, L
+
+
+# ------------------------------------------------------------------------- graph capture
+def test_forward_backward_and_decode_replay_from_a_graph():
+    """The library allocates nothing, records no memset and keeps no per-call state, so a captured
+    graph of its calls can be replayed on new data; every replay must equal the eager result bit
+    for bit (replays are interleaved with eager work and synchronisation)."""
+    T, d, F, K, B = 300, 256, 520, 65, 4
+    dt = torch.bfloat16
+    L = inputs.make_layer(92, T, d, F, "bf16", with_dy=True)
+    Gd = gpu_layer(L, "bf16")
+    x, dy = Gd["x"].clone(), Gd["dy"].clone()
+    xd = x[:B].clone()
+    ws_f = torch.empty(moc.workspace_bytes(T, d, F, K, dt, 0), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(moc.workspace_bytes(T, d, F, K, dt, 1), dtype=torch.uint8, device="cuda")
+    ws_d = torch.empty(moc.workspace_bytes(B, d, F, K, dt, 2), dtype=torch.uint8, device="cuda")
+    out_f = (torch.empty((T, d), dtype=dt, device="cuda"), torch.empty((T, K), dtype=torch.int32, device="cuda"),
+             torch.empty((T, K), dtype=dt, device="cuda"), torch.empty((T, K), dtype=dt, device="cuda"))
+    out_b = tuple(torch.empty(s, dtype=dt, device="cuda") for s in ((T, d), (F, d), (F, d), (F, d)))
+    out_d = (torch.empty((B, d), dtype=dt, device="cuda"), torch.empty((B, K), dtype=torch.int32, device="cuda"))
+
+    def run():
+        y, idx, gv, uv = moc.moc_ffn_fwd(x, Gd["wg"], Gd["wu"], Gd["wd"], K, ws=ws_f, out=out_f)
+        moc.moc_ffn_bwd(x, Gd["wg"], Gd["wu"], Gd["wd"], idx, gv, uv, dy, ws=ws_b, out=out_b)
+        moc.moc_ffn_decode(xd, Gd["wg"], Gd["wu"], Gd["wd"], K, ws=ws_d, out=out_d)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run()                                   # first calls set kernel attributes: outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        x.copy_(P.to_dev(inputs.normal((T, d), 9200 + rep, 1.0, "bf16"), "bf16"))
+        dy.copy_(P.to_dev(inputs.normal((T, d), 9210 + rep, 1.0, "bf16"), "bf16"))
+        xd.copy_(x[:B])
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (*out_f, *out_b, *out_d)]
+        for t in (*out_f, *out_b, *out_d):
+            t.zero_()
+        run()                                   # eager, same buffers
+        torch.cuda.synchronize()
+        for g, w in zip(got, (*out_f, *out_b, *out_d)):
+            assert torch.equal(g, w), "replay %d differs from the eager run" % rep
