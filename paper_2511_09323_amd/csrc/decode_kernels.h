@@ -219,76 +219,90 @@ __global__ __launch_bounds__(256) void decode_gate_group_kernel(const E* __restr
     }
 }
 
-// Gate projection for batches of 5..16 tokens on the matrix cores (bf16 only):
+// Gate projection for batches of 2..16 tokens on the matrix cores (bf16 only):
 //   g[b, j] = x[b] . wg[j]  as D[row j][token b] tiles of v_mfma_f32_16x16x32_bf16.
-// A 768-thread workgroup owns 48 consecutive channel rows (230 workgroups for 11008 rows, one per
-// CU): wave w works on row group w / 4 (16 rows) and on the quarter w % 4 of the contraction, so
-// 12 waves keep 12 x 8 KB of weights in flight per CU.  Lane l of a wave reads 32 contiguous bytes of row l % 16 per step (4 lanes cover
-// a 128-byte line); x[16, d] sits in LDS (rows padded by 16 bytes) and supplies the second MFMA
-// input with the same k assignment.  The four partial tiles of a row group are summed through LDS.
-// Needs d % 1024 == 0 (every wave's share is a whole number of 4-step prefetch groups).
+// A workgroup of RG * KS wavefronts owns 16 RG consecutive channel rows: wave w works on row group
+// w / KS (16 rows) and on share w % KS of the contraction, UN steps of 64 k (8 KB at UN = 4) in
+// flight per wave.  Lane l of a wave reads 32 contiguous bytes of row l % 16 per step (4 lanes cover
+// a 128-byte line); x[BTOK, d] sits in LDS (rows padded by 16 bytes) and supplies the second MFMA
+// input with the same k assignment (token slots from BTOK up are zero).  The KS partial tiles of a
+// row group are summed through LDS.  Needs d % (64 KS UN) == 0.
+// Two shapes are used: (RG 3, KS 4, BTOK 16, UN 4), 768 threads, 48 rows, one workgroup per CU because
+// x fills most of the LDS; and for at most four tokens (RG 1, KS 8, BTOK 4, UN 8), 512 threads, 16
+// rows, every load of a wave in flight at once and several workgroups per CU.
 // GB = 0 writes the gate rows g[B, ldg]; GB = 4, 8, 16 selects the a largest of every GB channels
-// instead (MoC_{a:b}; 48 rows are a whole number of groups) and writes idx / gsel [B, K] only.
+// instead (MoC_{a:b}; the rows of a workgroup are a whole number of groups) and writes idx / gsel
+// [B, K] only.
 typedef __bf16 dec_bf16x8_t __attribute__((ext_vector_type(8)));
-template <int GB>
-__global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __restrict__ x,
-                                                                const bf16_t* __restrict__ wg, int B, int d, int F,
-                                                                float* __restrict__ g, int64_t ldg, int ga, int K,
-                                                                int32_t* __restrict__ idx, float* __restrict__ gsel) {
+template <int GB, int RG, int KS, int BTOK, int UN>
+__global__ __launch_bounds__(RG * KS * 64) void decode_gate_mfma_kernel(const bf16_t* __restrict__ x,
+                                                                         const bf16_t* __restrict__ wg, int B, int d, int F,
+                                                                         float* __restrict__ g, int64_t ldg, int ga, int K,
+                                                                         int32_t* __restrict__ idx, float* __restrict__ gsel) {
+    constexpr int NT = RG * KS * 64, ROWS = RG * 16;
+    static_assert(GB == 0 || ROWS % GB == 0, "a workgroup's rows must be whole groups");
     extern __shared__ __align__(16) unsigned char dec_smem[];
     const int xpitch = d * 2 + 16;                                   // bytes per staged token row
-    float* red = reinterpret_cast<float*>(dec_smem + 16 * xpitch);   // [3 row groups][4 quarters][256]
+    float* red = reinterpret_cast<float*>(dec_smem + BTOK * xpitch); // [RG row groups][KS shares][256]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rg = wave >> 2, ks = wave & 3;
-    const int row0 = blockIdx.x * 48 + rg * 16;
-    const int kq = d / 4;                                            // contraction share of this wave
+    const int rg = wave / KS, ks = wave % KS;
+    const int row0 = blockIdx.x * ROWS + rg * 16;
+    const int kq = d / KS;                                           // contraction share of this wave
     const int q = lane >> 4;                                         // 16-element k sub-block of a 64-wide step
     const bf16_t* wrow = wg + (int64_t)min(row0 + (lane & 15), F - 1) * d + ks * kq + q * 16;
     // first weights in flight before x is staged
-    constexpr int UN = 4;                                            // steps of 64 k in flight (8 measured slower)
     u32x4_t w0[UN], w1[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
         w0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + u * 64));
         w1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + u * 64 + 8));
     }
-    for (int i = tid * 8; i < 16 * d; i += 768 * 8) {
+    for (int i = tid * 8; i < BTOK * d; i += NT * 8) {
         const int b = i / d, k = i - b * d;
         u32x4_t v = {0, 0, 0, 0};
         if (b < B) v = *reinterpret_cast<const u32x4_t*>(x + i);
         *reinterpret_cast<u32x4_t*>(dec_smem + b * xpitch + k * 2) = v;
     }
     __syncthreads();
-    const unsigned char* xl = dec_smem + (lane & 15) * xpitch + (ks * kq + q * 16) * 2;
+    const bool tok = (lane & 15) < BTOK;                             // this lane's token slot holds a token
+    const unsigned char* xl = dec_smem + (tok ? (lane & 15) : 0) * xpitch + (ks * kq + q * 16) * 2;
     f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
     const int nstep = kq / 64;
     for (int s0 = 0; s0 < nstep; s0 += UN) {
         u32x4_t c0[UN], c1[UN];
 #pragma unroll
         for (int u = 0; u < UN; ++u) { c0[u] = w0[u]; c1[u] = w1[u]; }
-        const int nxt = min(s0 + UN, nstep - UN);                    // clamped prefetch of the next UN steps
+        if (s0 + UN < nstep) {
+            const int nxt = min(s0 + UN, nstep - UN);                // clamped prefetch of the next UN steps
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            w0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64));
-            w1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64 + 8));
+            for (int u = 0; u < UN; ++u) {
+                w0[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64));
+                w1[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wrow + (nxt + u) * 64 + 8));
+            }
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             if (s0 + u < nstep) {
-                const dec_bf16x8_t x0 = *reinterpret_cast<const dec_bf16x8_t*>(xl + (s0 + u) * 128);
-                const dec_bf16x8_t x1 = *reinterpret_cast<const dec_bf16x8_t*>(xl + (s0 + u) * 128 + 16);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c0[u]), x0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c1[u]), x1, acc, 0, 0, 0);
+                u32x4_t x0 = {0, 0, 0, 0}, x1 = {0, 0, 0, 0};
+                if (BTOK == 16 || tok) {
+                    x0 = *reinterpret_cast<const u32x4_t*>(xl + (s0 + u) * 128);
+                    x1 = *reinterpret_cast<const u32x4_t*>(xl + (s0 + u) * 128 + 16);
+                }
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c0[u]),
+                                                              __builtin_bit_cast(dec_bf16x8_t, x0), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, c1[u]),
+                                                              __builtin_bit_cast(dec_bf16x8_t, x1), acc, 0, 0, 0);
             }
         }
     }
-    // acc[r] = D[row 4*(lane/16) + r][token lane % 16] over this wave's quarter of k
-    *reinterpret_cast<f32x4_t*>(red + ((rg * 4 + ks) * 64 + lane) * 4) = acc;
+    // acc[r] = D[row 4*(lane/16) + r][token lane % 16] over this wave's share of k
+    *reinterpret_cast<f32x4_t*>(red + ((rg * KS + ks) * 64 + lane) * 4) = acc;
     __syncthreads();
+    float* tile = red + RG * KS * 256;                               // [ROWS][17], grouped selection only
     if (ks == 0) {
         f32x4_t s = acc;
 #pragma unroll
-        for (int o = 1; o < 4; ++o) s += *reinterpret_cast<const f32x4_t*>(red + ((rg * 4 + o) * 64 + lane) * 4);
+        for (int o = 1; o < KS; ++o) s += *reinterpret_cast<const f32x4_t*>(red + ((rg * KS + o) * 64 + lane) * 4);
         const int b = lane & 15, r = row0 + 4 * (lane >> 4);
         if (GB == 0) {
             if (b < B) {
@@ -300,7 +314,6 @@ __global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __r
                 }
             }
         } else {
-            float* tile = red + 3 * 4 * 256;                       // [48 rows][17]
 #pragma unroll
             for (int e = 0; e < 4; ++e) tile[(rg * 16 + 4 * (lane >> 4) + e) * 17 + b] = s[e];
         }
@@ -308,13 +321,17 @@ __global__ __launch_bounds__(768) void decode_gate_mfma_kernel(const bf16_t* __r
     if (GB != 0) {
         __syncthreads();
         constexpr int GBS = GB == 0 ? 8 : GB;
-        const float* tile = red + 3 * 4 * 256;
-        const int grp = tid >> 4, b = tid & 15;                     // group of this workgroup's 48 rows, token
-        const int c0 = blockIdx.x * 48 + grp * GBS;
-        if (grp < 48 / GBS && b < B && c0 < F)
+        const int grp = tid >> 4, b = tid & 15;                     // group of this workgroup's rows, token
+        const int c0 = blockIdx.x * ROWS + grp * GBS;
+        if (grp < ROWS / GBS && b < B && c0 < F)
             decode_group_select<GBS>(tile + grp * GBS * 17 + b, 17, c0, c0 / GBS, ga, idx + (int64_t)b * K,
                                      gsel + (int64_t)b * K);
     }
+}
+
+// LDS bytes of decode_gate_mfma_kernel.
+inline size_t decode_gate_mfma_lds(int d, int RG, int KS, int BTOK) {
+    return (size_t)BTOK * (d * 2 + 16) + (size_t)RG * KS * 256 * sizeof(float) + (size_t)RG * 16 * 17 * sizeof(float);
 }
 
 // z[b, s] = SiLU(gsel[b, s]) * (x[b] . wu[idx[b, s]])  for every selected (token, channel) pair.

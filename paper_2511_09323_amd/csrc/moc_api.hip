@@ -582,10 +582,11 @@ moc_status decode_gate_group_b(const Dims& D, const E* x, const E* wg, int ga, i
     return decode_gate_group<E, BT, 16>(D, x, wg, ga, idx, gsel, st);
 }
 
-template <int GB>
-moc_status launch_decode_gate_mfma(const Dims& D, const bf16_t* x, const bf16_t* wg, float* g, int ga, int32_t* idx,
-                                   float* gsel, size_t lds, hipStream_t st) {
-    auto kern = decode_gate_mfma_kernel<GB>;
+template <int GB, int RG, int KS, int BTOK, int UN>
+moc_status launch_decode_gate_mfma_shape(const Dims& D, const bf16_t* x, const bf16_t* wg, float* g, int ga, int32_t* idx,
+                                         float* gsel, hipStream_t st) {
+    const size_t lds = decode_gate_mfma_lds(D.d, RG, KS, BTOK);
+    auto kern = decode_gate_mfma_kernel<GB, RG, KS, BTOK, UN>;
     static bool attr = false;
     if (!attr) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -593,10 +594,20 @@ moc_status launch_decode_gate_mfma(const Dims& D, const bf16_t* x, const bf16_t*
         attr = true;
     }
     Span span(GB == 0 ? "decode_gate" : "decode_gate_select", st);
-    hipLaunchKernelGGL(kern, dim3((D.F + 47) / 48), dim3(768), lds, st, x, wg, D.T, D.d, D.F, g, (int64_t)D.ldF, ga, D.K,
-                       idx, gsel);
+    const int rows = RG * 16;
+    hipLaunchKernelGGL(kern, dim3((D.F + rows - 1) / rows), dim3(RG * KS * 64), lds, st, x, wg, D.T, D.d, D.F, g,
+                       (int64_t)D.ldF, ga, D.K, idx, gsel);
     HIP_TRY(hipGetLastError());
     return MOC_OK;
+}
+
+// small = true: at most four tokens, d a multiple of 4096 (16 rows per workgroup, eight shares of the
+// contraction); otherwise up to 16 tokens, d a multiple of 1024 (48 rows, four shares).
+template <int GB>
+moc_status launch_decode_gate_mfma(const Dims& D, const bf16_t* x, const bf16_t* wg, float* g, int ga, int32_t* idx,
+                                   float* gsel, bool small, hipStream_t st) {
+    if (small) return launch_decode_gate_mfma_shape<GB, 1, 8, 4, 8>(D, x, wg, g, ga, idx, gsel, st);
+    return launch_decode_gate_mfma_shape<GB, 3, 4, 16, 4>(D, x, wg, g, ga, idx, gsel, st);
 }
 
 template <class E, int BT, int GA>
@@ -649,16 +660,20 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
         HIP_TRY(hipGetLastError());
         return MOC_OK;
     }
-    const size_t mfma_lds = (size_t)16 * (D.d * 2 + 16) + 4 * 4 * 256 * sizeof(float);
-    const bool mfma_gate = B > 4 && std::is_same<E, bf16_t>::value && D.d % 1024 == 0 && mfma_lds <= 160 * 1024 - 64 &&
-                           !options().force_generic;
-    if (mfma_gate) {
+    const bool bf16_mfma = std::is_same<E, bf16_t>::value && !options().force_generic;
+    // two to four tokens: the MFMA kernel's strided row reads stream slower than the row-per-wavefront
+    // GEMV (26.7 against 24.8 us at the 7B shape), but with the selection fused in it beats the
+    // workgroup-per-group GEMV (28.3 against 30.8 us), so it serves the grouped variant only
+    const bool mfma_small = bf16_mfma && gb != 0 && B >= 2 && B <= 4 && D.d % 4096 == 0 &&
+                            decode_gate_mfma_lds(D.d, 1, 8, 4) <= 64 * 1024;
+    const bool mfma_large = bf16_mfma && B > 4 && D.d % 1024 == 0 && decode_gate_mfma_lds(D.d, 3, 4, 16) <= 160 * 1024 - 64;
+    if (mfma_small || mfma_large) {
         const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
         const bf16_t* wb = reinterpret_cast<const bf16_t*>(wg);
-        if (gb == 0) s = launch_decode_gate_mfma<0>(D, xb, wb, W.g, 0, idx, W.gsel, mfma_lds, st);
-        else if (gb == 4) s = launch_decode_gate_mfma<4>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
-        else if (gb == 8) s = launch_decode_gate_mfma<8>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
-        else s = launch_decode_gate_mfma<16>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_lds, st);
+        if (gb == 0) s = launch_decode_gate_mfma<0>(D, xb, wb, W.g, 0, idx, W.gsel, mfma_small, st);
+        else if (gb == 4) s = launch_decode_gate_mfma<4>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_small, st);
+        else if (gb == 8) s = launch_decode_gate_mfma<8>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_small, st);
+        else s = launch_decode_gate_mfma<16>(D, xb, wb, W.g, ga, idx, W.gsel, mfma_small, st);
     } else if (gb == 0) {
         if (B == 1) s = decode_gate<E, 1>(D, x, wg, W.g, st);
         else if (B <= 4) s = decode_gate<E, 4>(D, x, wg, W.g, st);
