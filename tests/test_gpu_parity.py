@@ -338,3 +338,18 @@ def test_forward_backward_and_decode_replay_from_a_graph():
         torch.cuda.synchronize()
         for g, w in zip(got, (*out_f, *out_b, *out_d)):
             assert torch.equal(g, w), "replay %d differs from the eager run" % rep
+
+
+def test_generic_kernels_serve_bf16_when_forced():
+    """MOC_FORCE_GENERIC=1 (read once per process, hence the child process) routes every bf16 GEMM to the
+    fp32-FMA kernel and decode to its non-MFMA kernels; results must still match the oracle."""
+    import os
+    import subprocess
+    code = ("import tests.test_gpu_parity as t\n"
+            "t.run_fwd_bwd_case('forced-generic', 91, 150, 128, 330, 41, 'bf16')\n"
+            "t.run_decode_case('forced-generic', 91, 9, 1024, 336, 42, 'bf16')\n"
+            "print('ok')\n")
+    env = dict(os.environ, MOC_FORCE_GENERIC="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-2000:] + r.stderr[-2000:]
