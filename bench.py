@@ -218,6 +218,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
 
+    line_clocks = gpu_clocks()
     line = {
         "metric": "MoC FFN fwd+bwd tokens/s (1B shape) + decode effective HBM GB/s vs peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -226,9 +227,25 @@ def main():
         "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
                    "T": T, "d_model": d, "d_ff": F, "K": K},
         "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
-        "decode": decode, "prefill_stack": stack, "grouped_2of8": grouped,
+        "decode": decode, "prefill_stack": stack, "grouped_2of8": grouped, "clocks_after_run": line_clocks,
     }
     print(json.dumps(line))
+
+
+def gpu_clocks():
+    """Shader and memory clock as rocm-smi reports them right after the timed work (best effort)."""
+    import re
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+        got = {}
+        for key in ("sclk", "mclk", "fclk"):
+            m = re.search(key + r" clock level: \d+: \((\d+)Mhz\)", out)
+            if m:
+                got[key + "_MHz"] = int(m.group(1))
+        return got or None
+    except Exception:
+        return None
 
 
 def stack_leg(torch, moc, cfg, dev, layers=32):
@@ -361,7 +378,7 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev, group=None):
             unions.append(int(torch.unique(idx).numel()))
         union = float(np.mean(unions))
         algo_bytes = d * F * 2 + 2 * union * d * 2 + 2 * B * d * 2
-        iters = 5 * R
+        iters = 7 * R                   # 56 cold calls
         start = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
         stop = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
         for i in range(iters):
