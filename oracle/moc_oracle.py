@@ -16,6 +16,8 @@ What each function follows:
                            the definition before Theorem 1): a entries are kept in every contiguous
                            group of b entries of a row; b divides d_ffn.
   moc_forward_grouped, moc_decode_grouped   the same layer and recipe with that mask.
+  selection_key, topk_mask_keyed, moc_forward_keyed   the Top-K position variants of the ablation
+                           ("After SiLU") and of the proof of Theorem 1 (|SiLU|).
   moc_forward*             Eqs. (MoC-1), (MoC-2).
   moc_backward             Section "Activation-efficient pre-training", Eqs. (bp-1)...(bp-5),
                            with S' and Z' recomputed from the stored G.M and U.M (MoC + GCP).
@@ -34,7 +36,9 @@ silu at K = d_ffn, torch.autograd and central finite differences for the backwar
 rms_norm, and the invariants (unselected channels contribute nothing, token independence,
 channel-permutation equivariance, decode == training forward); for the grouped mask: a hand example,
 the loop twin, b = d_ffn reducing to topk_mask, a = b reducing to dense SwiGLU, torch.topk on the
-reshaped row, exactly a per group, the 2:4 compatibility of 2:8 masks.  No function here is unpinned.
+reshaped row, exactly a per group, the 2:4 compatibility of 2:8 masks; for the keyed masks: monotonicity of
+SiLU above its minimum (same set as the raw gate when the threshold is positive), hand cases below it, torch.topk on
+torch's own silu.  No function here is unpinned.
 """
 import numpy as np
 
@@ -101,6 +105,36 @@ def topk_mask(G, K, select_dtype=np.float32):
         order = np.argsort(-key[i], kind="stable")
         M[i, order[:K]] = True
     return M
+
+
+def selection_key(G, key="gate", select_dtype=np.float32):
+    """What the Top-K ranks.  "gate": the raw signed SiLU input (the paper's choice, section
+    "Mixture-of-Channels architecture"); "silu": the SiLU output, signed (ablation "Effect of top-K's
+    position", row "After SiLU"); "abs_silu": its absolute value (the selection used in the proof of
+    Theorem 1, see the remark after it).  The gate is first rounded to `select_dtype`, the precision
+    the selection is decided in, and so is the transformed key."""
+    g = np.asarray(G).astype(select_dtype)
+    if key == "gate":
+        return g
+    s = silu(g.astype(F64))
+    if key == "silu":
+        return s.astype(select_dtype)
+    if key == "abs_silu":
+        return np.abs(s).astype(select_dtype)
+    raise ValueError("unknown selection key %r" % (key,))
+
+
+def topk_mask_keyed(G, K, key="gate"):
+    """topk_mask on selection_key(G, key): exactly K ones per row, ties to the lower channel."""
+    return topk_mask(selection_key(G, key), K)
+
+
+def moc_forward_keyed(X, W_gate, W_up, W_down, K, key):
+    """Eqs. (MoC-1), (MoC-2) with the mask taken on selection_key(G, key) instead of on G."""
+    G = _f64(X) @ _f64(W_gate)
+    M = topk_mask_keyed(G, K, key)
+    D, G, U = moc_forward_given_mask(X, W_gate, W_up, W_down, M)
+    return D, M, G, U
 
 
 def grouped_topk_mask(G, a, b, select_dtype=np.float32):

@@ -359,3 +359,44 @@ def test_grouped_forward_reductions_and_twin():
     Wu2[:, never] = 1e6
     Wd2[never, :] = -1e6
     np.testing.assert_array_equal(O.moc_forward_given_mask(X, Wg, Wu2, Wd2, M28)[0], D28)
+
+
+# ------------------------------------------------- Top-K position variants (keyed selection)
+def test_selection_key_hand_cases():
+    # SiLU has its minimum at x = -1.2785 (value -0.2785): below it the order reverses.
+    g = np.array([[-6.0, -1.3, -0.5, 0.05, 0.3, -3.0]])
+    s = g / (1 + np.exp(-g))                     # [-0.0148, -0.2784, -0.1888, 0.0256, 0.1723, -0.1423]
+    assert list(np.flatnonzero(O.topk_mask_keyed(g, 3, "gate")[0])) == [2, 3, 4]
+    assert list(np.flatnonzero(O.topk_mask_keyed(g, 3, "silu")[0])) == [0, 3, 4]          # -6 beats -0.5 after SiLU
+    assert list(np.flatnonzero(O.topk_mask_keyed(g, 3, "abs_silu")[0])) == [1, 2, 4]      # largest |SiLU|
+    np.testing.assert_allclose(O.selection_key(g, "silu")[0], s[0].astype(np.float32), rtol=1e-6)
+    np.testing.assert_allclose(O.selection_key(g, "abs_silu")[0], np.abs(s[0]).astype(np.float32), rtol=1e-6)
+    with pytest.raises(ValueError):
+        O.selection_key(g, "nonsense")
+
+
+def test_keyed_masks_against_library_routines_and_monotonicity():
+    rng = np.random.default_rng(31)
+    G = (rng.standard_normal((23, 300)) * 1.5).astype(np.float32)
+    for key in ("silu", "abs_silu"):
+        for K in (1, 17, 150, 299):
+            M = O.topk_mask_keyed(G, K, key)
+            assert np.all(M.sum(axis=1) == K)
+            st = torch.nn.functional.silu(torch.from_numpy(G).double())
+            if key == "abs_silu":
+                st = st.abs()
+            tv = torch.topk(st.float(), K, dim=1).values.numpy()
+            kept = np.sort(np.where(M, st.float().numpy(), -np.inf), axis=1)[:, 300 - K:]
+            np.testing.assert_array_equal(np.sort(tv, axis=1), kept)
+    # while the K-th largest gate value is above SiLU's minimiser, "silu" selects what "gate" selects
+    for K in (5, 40, 100):
+        kth = np.sort(G, axis=1)[:, 300 - K]
+        rows = kth > -1.0
+        assert rows.any()
+        np.testing.assert_array_equal(O.topk_mask_keyed(G, K, "silu")[rows], O.topk_mask(G, K)[rows])
+    # forward through the keyed mask: same as the given-mask forward
+    X, Wg, Wu, Wd = _rand_layer(8, 7, 6, 24)
+    D, M, Gm, U = O.moc_forward_keyed(X, Wg, Wu, Wd, 9, "abs_silu")
+    np.testing.assert_array_equal(D, O.moc_forward_given_mask(X, Wg, Wu, Wd, M)[0])
+    np.testing.assert_array_equal(M, O.topk_mask_keyed(Gm, 9, "abs_silu"))
+    np.testing.assert_array_equal(O.moc_forward_keyed(X, Wg, Wu, Wd, 9, "gate")[0], O.moc_forward(X, Wg, Wu, Wd, 9)[0])
