@@ -60,8 +60,14 @@ typedef enum {
     MOC_OP_BWD = 1,
     MOC_OP_DECODE = 2,
     MOC_OP_SWIGLU_FWD = 3,
-    MOC_OP_SWIGLU_BWD = 4
+    MOC_OP_SWIGLU_BWD = 4,
+    MOC_OP_FWD_KEYED = 5       /* moc_ffn_fwd_keyed: the forward workspace plus one fp32 [T, F] key array */
 } moc_op;
+
+/* What the row Top-K ranks (ablation "Effect of top-K's position" and the remark after the proof
+ * of Theorem 1): the raw gate (the paper's choice and the default everywhere else), the SiLU
+ * output, or its absolute value. */
+typedef enum { MOC_KEY_GATE = 0, MOC_KEY_SILU = 1, MOC_KEY_ABS_SILU = 2 } moc_key;
 
 /* T tokens (batch for decode), d = d_model, F = d_ffn, K selected channels per token. */
 typedef struct {
@@ -110,6 +116,24 @@ moc_status moc_swiglu_bwd(const moc_shape* shape, const void* x, const void* wg,
  * aligned 16-byte block that holds the last element of a row is read whole. */
 moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_t ldg,
                          int32_t* idx, float* gsel, void* hip_stream);
+
+/* Top-K position variants: as moc_ffn_fwd / moc_ffn_decode / moc_topk_rows, but the K channels of
+ * a row are those with the largest key_mode(g) (moc_key); gvals / gsel still hold the gate values
+ * themselves, so moc_ffn_bwd takes the stored set unchanged.  key_mode = MOC_KEY_GATE is the plain
+ * call.  moc_ffn_fwd_keyed needs moc_workspace_bytes(shape, MOC_OP_FWD_KEYED); moc_topk_rows_keyed
+ * needs key_scratch, caller-owned fp32 [T, ldg] (unused, may be NULL, for MOC_KEY_GATE).  The
+ * keys are computed in fp32 from the fp32 gate; ties and signed zeros as everywhere else. */
+moc_status moc_ffn_fwd_keyed(const moc_shape* shape, int32_t key_mode, const void* x, const void* wg,
+                             const void* wu, const void* wd, void* y, int32_t* idx, void* gvals,
+                             void* uvals, void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_ffn_decode_keyed(const moc_shape* shape, int32_t key_mode, const void* x,
+                                const void* wg, const void* wu, const void* wd, void* y,
+                                int32_t* idx_or_null, void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_topk_rows_keyed(int32_t T, int32_t F, int32_t K, int32_t key_mode, const float* g,
+                               int64_t ldg, float* key_scratch, int32_t* idx, float* gsel,
+                               void* hip_stream);
 
 /* MoC_{a:b}, the grouped Top-K variant (item "MoC with structured 2:8 sparsity" of section
  * "Mixture-of-Channels architecture"; a:b defined before Theorem 1): the mask keeps the a largest

@@ -18,7 +18,7 @@ OP_FWD, OP_BWD, OP_DECODE, OP_SWIGLU_FWD, OP_SWIGLU_BWD = range(5)
 
 EXPORTS = (
     "moc_workspace_bytes", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
-    "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
+    "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_keyed", "moc_ffn_decode_keyed", "moc_topk_rows_keyed", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
     "moc_timing_collect", "moc_timing_get", "moc_timing_reset", "moc_status_string",
     "moc_last_error", "moc_version",
 )
@@ -62,6 +62,12 @@ def load_library():
     lib.moc_swiglu_bwd.argtypes = [shp] + [vp] * 12 + [sz, vp]
     lib.moc_topk_rows.restype = ctypes.c_int
     lib.moc_topk_rows.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp]
+    lib.moc_ffn_fwd_keyed.restype = ctypes.c_int
+    lib.moc_ffn_fwd_keyed.argtypes = [shp, i32] + [vp] * 9 + [sz, vp]
+    lib.moc_ffn_decode_keyed.restype = ctypes.c_int
+    lib.moc_ffn_decode_keyed.argtypes = [shp, i32] + [vp] * 7 + [sz, vp]
+    lib.moc_topk_rows_keyed.restype = ctypes.c_int
+    lib.moc_topk_rows_keyed.argtypes = [i32, i32, i32, i32, vp, i64, vp, vp, vp, vp]
     lib.moc_ffn_fwd_grouped.restype = ctypes.c_int
     lib.moc_ffn_fwd_grouped.argtypes = [shp, i32, i32] + [vp] * 9 + [sz, vp]
     lib.moc_ffn_decode_grouped.restype = ctypes.c_int
@@ -270,6 +276,76 @@ def moc_topk_rows(g, K):
     idx = torch.empty((T, K), dtype=torch.int32, device=g.device)
     gsel = torch.empty((T, K), dtype=torch.float32, device=g.device)
     _check(lib.moc_topk_rows(T, F, K, ctypes.c_void_p(g.data_ptr()), ldg, _ptr(idx), _ptr(gsel), _stream()))
+    return idx, gsel
+
+
+KEY_MODES = {"gate": 0, "silu": 1, "abs_silu": 2}
+OP_FWD_KEYED = 5
+
+
+def _key_code(key):
+    if key not in KEY_MODES:
+        raise MocError("MOC_ERR_BAD_ARG", "selection key must be one of %s" % sorted(KEY_MODES))
+    return KEY_MODES[key]
+
+
+def moc_ffn_fwd_keyed(x, wg, wu, wd, K, key, ws=None, out=None):
+    """moc_ffn_fwd with the Top-K taken on key(g): "gate" (plain), "silu" or "abs_silu".
+    Returns (y, idx, gvals, uvals); gvals are the gate values themselves."""
+    lib = load_library()
+    T, d = x.shape
+    F = wg.shape[0]
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((T, d), dtype=dt, device=x.device)
+        idx = torch.empty((T, K), dtype=torch.int32, device=x.device)
+        gvals = torch.empty((T, K), dtype=dt, device=x.device)
+        uvals = torch.empty((T, K), dtype=dt, device=x.device)
+    else:
+        y, idx, gvals, uvals = out
+    ws, ws_bytes = _workspace(ws, T, d, F, K, dt, OP_FWD_KEYED, x.device)
+    shp = _shape(T, d, F, K, code)
+    _check(lib.moc_ffn_fwd_keyed(ctypes.byref(shp), _key_code(key), _ptr(x, dt, (T, d), "x"), _ptr(wg, dt, (F, d), "wg"),
+                                 _ptr(wu, dt, (F, d), "wu"), _ptr(wd, dt, (F, d), "wd"), _ptr(y, dt, (T, d), "y"),
+                                 _ptr(idx, torch.int32, (T, K), "idx"), _ptr(gvals, dt, (T, K), "gvals"),
+                                 _ptr(uvals, dt, (T, K), "uvals"), _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return y, idx, gvals, uvals
+
+
+def moc_ffn_decode_keyed(x, wg, wu, wd, K, key, ws=None, want_idx=True, out=None):
+    """moc_ffn_decode with the Top-K taken on key(g).  Returns (y, idx or None)."""
+    lib = load_library()
+    B, d = x.shape
+    F = wg.shape[0]
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((B, d), dtype=dt, device=x.device)
+        idx = torch.empty((B, K), dtype=torch.int32, device=x.device) if want_idx else None
+    else:
+        y, idx = out
+    ws, ws_bytes = _workspace(ws, B, d, F, K, dt, OP_DECODE, x.device)
+    shp = _shape(B, d, F, K, code)
+    _check(lib.moc_ffn_decode_keyed(ctypes.byref(shp), _key_code(key), _ptr(x, dt, (B, d), "x"), _ptr(wg, dt, (F, d), "wg"),
+                                    _ptr(wu, dt, (F, d), "wu"), _ptr(wd, dt, (F, d), "wd"), _ptr(y, dt, (B, d), "y"),
+                                    _ptr(idx, torch.int32, (B, K), "idx") if idx is not None else None,
+                                    _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return y, idx
+
+
+def moc_topk_rows_keyed(g, K, key):
+    """Row-wise Top-K of key(g) for an fp32 matrix g [T,F].  Returns (idx ascending, gsel = g there)."""
+    lib = load_library()
+    T, F = g.shape
+    if not g.is_cuda or g.dtype != torch.float32 or g.stride(1) != 1:
+        raise MocError("MOC_ERR_BAD_ARG", "g must be a GPU fp32 matrix with unit column stride")
+    ldg = g.stride(0) if T > 1 else F
+    idx = torch.empty((T, K), dtype=torch.int32, device=g.device)
+    gsel = torch.empty((T, K), dtype=torch.float32, device=g.device)
+    scratch = torch.empty((T, ldg), dtype=torch.float32, device=g.device)
+    _check(lib.moc_topk_rows_keyed(T, F, K, _key_code(key), ctypes.c_void_p(g.data_ptr()), ldg, _ptr(scratch), _ptr(idx),
+                                   _ptr(gsel), _stream()))
     return idx, gsel
 
 

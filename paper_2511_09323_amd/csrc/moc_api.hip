@@ -372,17 +372,27 @@ struct Dims {
 };
 
 template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gate, U, masked Z'
-    float* G;
+    float *G, *keys;                   // keys: transformed selection keys (Top-K position variants only)
     E *U, *Zd;
     size_t bytes;
-    FwdWs(void* ws, const Dims& D, bool dense) {
+    FwdWs(void* ws, const Dims& D, bool dense, bool keyed = false) {
         Carver c(ws);
         G = dense ? nullptr : c.take<float>((size_t)D.T * D.ldF);
         U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
         Zd = c.take<E>((size_t)D.T * D.ldF);
+        keys = keyed ? c.take<float>((size_t)D.T * D.ldF) : nullptr;
         bytes = c.off;
     }
 };
+
+// keys = SiLU(g) or |SiLU(g)| over n contiguous fp32 values (Top-K position variants)
+moc_status launch_key_transform(const float* g, float* keys, int64_t n, int key_mode, hipStream_t st) {
+    Span span("topk_key_transform", st);
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, 16384));
+    hipLaunchKernelGGL(topk_key_transform_kernel, dim3(grid), dim3(256), 0, st, g, keys, n, key_mode);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
 
 template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mask of the fallback path)
     uint32_t* maskw;
@@ -412,12 +422,13 @@ int decode_splits(int B, int K) {
 constexpr int kDecodeFusedMaxP = 512;
 
 struct DecodeWs {
-    float *g, *gsel, *z, *part;
+    float *g, *gkeys, *gsel, *z, *part;
     int32_t* idx;
     size_t bytes;
     DecodeWs(void* ws, const Dims& D) {
         Carver c(ws);
         g = c.take<float>((size_t)D.T * D.ldF);
+        gkeys = c.take<float>((size_t)D.T * D.ldF);
         gsel = c.take<float>((size_t)D.T * D.K);
         z = c.take<float>((size_t)D.T * D.K);
         idx = c.take<int32_t>((size_t)D.T * D.K);
@@ -435,6 +446,7 @@ template <class E> size_t workspace_for(const Dims& D, int op) {
         case MOC_OP_DECODE: return DecodeWs(nullptr, D).bytes;
         case MOC_OP_SWIGLU_FWD: return FwdWs<E>(nullptr, D, true).bytes;
         case MOC_OP_SWIGLU_BWD: return BwdWs<E>(nullptr, D, true).bytes;
+        case MOC_OP_FWD_KEYED: return FwdWs<E>(nullptr, D, false, true).bytes;
     }
     return 0;
 }
@@ -449,8 +461,8 @@ moc_status down_projection(const Dims& D, const E* Zd, const E* wd, E* y, hipStr
 // ----------------------------------------------------------------------------- forward
 template <class E>
 moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx, E* gvals,
-                    E* uvals, void* ws, hipStream_t st, int ga = 0, int gb = 0) {
-    FwdWs<E> W(ws, D, false);
+                    E* uvals, void* ws, hipStream_t st, int ga = 0, int gb = 0, int key_mode = 0) {
+    FwdWs<E> W(ws, D, false, key_mode != 0);
     moc_status s;
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
     // and U = X W_up (Eq. MoC-1): one launch for both when possible
@@ -460,7 +472,13 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                               EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK)
         return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
-    TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF};
+    TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF, nullptr};
+    if (key_mode != 0) {
+        // rank SiLU(G) or |SiLU(G)| instead of G; the stored gate values stay the raw ones
+        if ((s = launch_key_transform(W.G, W.keys, (int64_t)D.T * D.ldF, key_mode, st)) != MOC_OK) return s;
+        a.g = W.keys;
+        a.g_raw = W.G;
+    }
     // 256 threads per row keep up to 24 values per thread in registers; longer rows get 512 threads
     // (1024 measured slower)
     if (gb == 0) s = D.ldF > 6144 ? run_topk<E, 512, true>("topk_select_act", a, D.T, st)
@@ -638,7 +656,7 @@ moc_status launch_decode_fused(const Dims& D, const E* x, const E* wg, const E* 
 // inside the gate kernel (a group's channels meet in one workgroup) and needs no selection launch.
 template <class E>
 moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx_out,
-                       void* ws, hipStream_t st, int ga = 0, int gb = 0) {
+                       void* ws, hipStream_t st, int ga = 0, int gb = 0, int key_mode = 0) {
     DecodeWs W(ws, D);
     const int B = D.T;
     int32_t* idx = idx_out ? idx_out : W.idx;
@@ -685,7 +703,12 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     }
     if (s != MOC_OK) return s;
     if (gb == 0) {
-        TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+        TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr};
+        if (key_mode != 0) {
+            if ((s = launch_key_transform(W.g, W.gkeys, (int64_t)B * D.ldF, key_mode, st)) != MOC_OK) return s;
+            a.g = W.gkeys;
+            a.g_raw = W.g;
+        }
         if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
     }
     const int P = decode_splits(B, D.K);
@@ -734,7 +757,7 @@ extern "C" {
 
 size_t moc_workspace_bytes(const moc_shape* shape, int op) {
     if (check_shape(shape, op == MOC_OP_DECODE) != MOC_OK) return 0;
-    if (op < MOC_OP_FWD || op > MOC_OP_SWIGLU_BWD) return 0;
+    if (op < MOC_OP_FWD || op > MOC_OP_FWD_KEYED) return 0;
     Dims D(*shape);
     return shape->dtype == MOC_BF16 ? workspace_for<bf16_t>(D, op) : workspace_for<float>(D, op);
 }
@@ -846,6 +869,65 @@ moc_status moc_topk_rows(int32_t T, int32_t F, int32_t K, const float* g, int64_
     CHECK_PTR(g); CHECK_PTR(idx); CHECK_PTR(gsel);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     TopkArgs<float> a{g, ldg, F, K, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0};
+    return run_topk<float, 256, false>("topk_rows", a, T, st);
+}
+
+static moc_status check_key_mode(int32_t key_mode) {
+    if (key_mode < MOC_KEY_GATE || key_mode > MOC_KEY_ABS_SILU) return fail(MOC_ERR_BAD_ARG, "unknown selection key %d", key_mode);
+    return MOC_OK;
+}
+
+moc_status moc_ffn_fwd_keyed(const moc_shape* shape, int32_t key_mode, const void* x, const void* wg, const void* wu,
+                             const void* wd, void* y, int32_t* idx, void* gvals, void* uvals, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    if ((s = check_key_mode(key_mode)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_WS(MOC_OP_FWD_KEYED);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return fwd_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd, (bf16_t*)y,
+                                idx, (bf16_t*)gvals, (bf16_t*)uvals, ws, st, 0, 0, key_mode);
+    return fwd_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y, idx,
+                           (float*)gvals, (float*)uvals, ws, st, 0, 0, key_mode);
+}
+
+moc_status moc_ffn_decode_keyed(const moc_shape* shape, int32_t key_mode, const void* x, const void* wg, const void* wu,
+                                const void* wd, void* y, int32_t* idx_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, true);
+    if (s != MOC_OK) return s;
+    if ((s = check_key_mode(key_mode)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y);
+    if (idx_or_null && !aligned16(idx_or_null)) return fail(MOC_ERR_BAD_ARG, "idx is not 16-byte aligned");
+    CHECK_WS(MOC_OP_DECODE);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return decode_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                   (bf16_t*)y, idx_or_null, ws, st, 0, 0, key_mode);
+    return decode_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y,
+                              idx_or_null, ws, st, 0, 0, key_mode);
+}
+
+moc_status moc_topk_rows_keyed(int32_t T, int32_t F, int32_t K, int32_t key_mode, const float* g, int64_t ldg,
+                               float* key_scratch, int32_t* idx, float* gsel, void* hip_stream) {
+    if (T < 1 || F < 1 || K < 1 || K > F) return fail(MOC_ERR_BAD_ARG, "need T >= 1 and 1 <= K <= F (T=%d F=%d K=%d)", T, F, K);
+    if (F > 32768) return fail(MOC_ERR_UNSUPPORTED, "F = %d exceeds 32768", F);
+    if (ldg < F) return fail(MOC_ERR_BAD_ARG, "ldg < F");
+    moc_status s = check_key_mode(key_mode);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(g); CHECK_PTR(idx); CHECK_PTR(gsel);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    TopkArgs<float> a{g, ldg, F, K, idx, gsel, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr};
+    if (key_mode != MOC_KEY_GATE) {
+        CHECK_PTR(key_scratch);
+        // the last row is transformed up to F only: nothing past the caller's matrix is read
+        if ((s = launch_key_transform(g, key_scratch, (int64_t)(T - 1) * ldg + F, key_mode, st)) != MOC_OK) return s;
+        a.g = key_scratch;
+        a.g_raw = g;
+    }
     return run_topk<float, 256, false>("topk_rows", a, T, st);
 }
 

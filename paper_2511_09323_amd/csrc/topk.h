@@ -42,7 +42,19 @@ template <class E> struct TopkArgs {
     E* uvals;           // [T, K]
     E* zd;              // [T, ldz] dense masked activation
     int64_t ldz;
+    // Keyed selection (Top-K position variants): g then holds the transformed keys the ranking is
+    // done on, and the gate values themselves are fetched from here ([T, ldg] like g); null otherwise.
+    const float* g_raw;
 };
+
+// Selection keys of the Top-K position variants: mode 1 ranks SiLU(g) (ablation row "After SiLU"),
+// mode 2 ranks |SiLU(g)| (the selection of the proof of Theorem 1).  Element-wise, [T, ld] fp32.
+__global__ void topk_key_transform_kernel(const float* __restrict__ g, float* __restrict__ keys, int64_t n, int mode) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float s = silu_f32(g[i]);
+        keys[i] = mode == 2 ? fabsf(s) : s;
+    }
+}
 
 // Exclusive scan of one value per thread across the workgroup, in thread order.
 // red must hold NT/64 ints.  Returns the exclusive prefix; total goes to *total.
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
             z[e] = 0.0f;
             if (sel) {
                 const int slot = gt_before + min(eq_before, need);
-                const float g = key_float(k[e]);
+                const float g = a.g_raw ? a.g_raw[row * a.ldg + j0 + e] : key_float(k[e]);
                 idx_row[slot] = j0 + e;
                 if (a.gsel_f32) a.gsel_f32[row * K + slot] = g;
                 if (a.gvals) Elem<E>::store(a.gvals + row * K + slot, g);
@@ -537,7 +549,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
     // ---- write the compact outputs slot by slot (coalesced) and scatter z' into the dense row
     for (int sl = tid; sl < K; sl += NT) {
         const int j = min((int)rec[3 * sl], F - 1);       // the clamp only matters for non-finite input
-        const float g = key_float(rec[3 * sl + 1]);
+        const float g = a.g_raw ? a.g_raw[row * a.ldg + j] : key_float(rec[3 * sl + 1]);
         a.idx[row * K + sl] = j;
         if (a.gsel_f32) a.gsel_f32[row * K + sl] = g;
         if (a.gvals) Elem<E>::store(a.gvals + row * K + sl, g);

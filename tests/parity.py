@@ -118,3 +118,26 @@ def check_grouped_index_sets(idx_gpu, G64, a, b):
             assert np.all(kept[grp > tau + tol]), "row %d group %d drops a channel clearly above the threshold" % (t, q)
             assert not np.any(kept[grp < tau - tol]), "row %d group %d keeps a channel clearly below it" % (t, q)
     return differing
+
+
+def check_keyed_index_sets(idx_gpu, G64, K, key):
+    """check_index_sets for the Top-K position variants: the ranking, the threshold and the near-tie
+    window (1e-6 relative to the larger of |threshold| and the row's RMS key, because SiLU outputs of
+    negative gates cluster near zero) are those of the oracle's float32 selection key."""
+    idx_gpu = np.asarray(idx_gpu)
+    T, F = G64.shape
+    assert idx_gpu.shape == (T, K)
+    assert np.all(idx_gpu >= 0) and np.all(idx_gpu < F)
+    if K > 1:
+        assert np.all(np.diff(idx_gpu, axis=1) > 0), "idx rows must ascend strictly"
+    keys = O.selection_key(G64, key).astype(np.float64)
+    M_ref = O.topk_mask_keyed(G64, K, key)
+    M_gpu = O.mask_from_idx(idx_gpu, F)
+    differing = np.flatnonzero((M_ref != M_gpu).any(axis=1))
+    for t in differing:
+        row = keys[t]
+        tau = np.sort(row)[F - K]
+        tol = TIE_WINDOW * max(abs(tau), float(np.sqrt(np.mean(row ** 2))), 1e-30)
+        assert np.all(M_gpu[t][row > tau + tol]), "row %d drops a channel clearly above the threshold" % t
+        assert not np.any(M_gpu[t][row < tau - tol]), "row %d keeps a channel clearly below the threshold" % t
+    return differing

@@ -90,6 +90,12 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert rc == -3
     assert lib.moc_topk_rows(4, 16, 17, fake, 16, fake, fake, None) == -1
     assert lib.moc_topk_rows(4, 16, 4, fake, 8, fake, fake, None) == -1     # ldg < F
+    s = B.MocShape(4, 64, 128, 16, B.MOC_BF16)
+    assert lib.moc_ffn_fwd_keyed(ctypes.byref(s), 3, *([fake] * 9), 1 << 30, None) == -1          # unknown key
+    assert lib.moc_ffn_fwd_keyed(ctypes.byref(s), 1, *([fake] * 9), 16, None) == -2               # short workspace
+    assert lib.moc_ffn_decode_keyed(ctypes.byref(s), -1, *([fake] * 7), 1 << 30, None) == -1
+    assert lib.moc_topk_rows_keyed(4, 16, 4, 1, fake, 16, None, fake, fake, None) == -1            # keyed needs key_scratch
+    assert _ws(lib, 4, 64, 128, 16, B.MOC_BF16, 5) > _ws(lib, 4, 64, 128, 16, B.MOC_BF16, B.OP_FWD)
     # grouped Top-K (MoC_{a:b}): b in {4, 8, 16} dividing F, 1 <= a <= b, K = a F / b
     s = B.MocShape(4, 64, 128, 32, B.MOC_BF16)
     for a, b in ((2, 8), ):
