@@ -127,3 +127,13 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_committed_traffic_summary_has_the_roofline_kernel():
+    # bench.py takes roofline.traffic from this file; a renamed kernel must not silently drop it
+    import json
+    tj = json.load(open(os.path.join(ROOT, "profiles", "cfg2_traffic.json")))
+    ent = tj["gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>"]
+    assert ent["hbm_read_bytes"] > 0 and ent["hbm_written_bytes"] > 0
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    assert "gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>" in src
