@@ -16,6 +16,8 @@ What each function follows:
                            the definition before Theorem 1): a entries are kept in every contiguous
                            group of b entries of a row; b divides d_ffn.
   moc_forward_grouped, moc_decode_grouped   the same layer and recipe with that mask.
+  moc_forward_experts, moc_backward_experts   Section "Compatibility with MoE architectures": the
+                           MoC network as the MLP of every expert, on rows already routed.
   selection_key, topk_mask_keyed, moc_forward_keyed   the Top-K position variants of the ablation
                            ("After SiLU") and of the proof of Theorem 1 (|SiLU|).
   moc_forward*             Eqs. (MoC-1), (MoC-2).
@@ -38,7 +40,8 @@ channel-permutation equivariance, decode == training forward); for the grouped m
 the loop twin, b = d_ffn reducing to topk_mask, a = b reducing to dense SwiGLU, torch.topk on the
 reshaped row, exactly a per group, the 2:4 compatibility of 2:8 masks; for the keyed masks: monotonicity of
 SiLU above its minimum (same set as the raw gate when the threshold is positive), hand cases below it, torch.topk on
-torch's own silu.  No function here is unpinned.
+torch's own silu; for the expert form: one expert equals the plain layer, a dense Mixtral-style layer written with
+torch ops at K = d_ffn, row-wise single-token evaluation, finite differences.  No function here is unpinned.
 """
 import numpy as np
 
@@ -300,6 +303,51 @@ def decode_macs(d, d_ffn, K):
 def stored_activation_elements(s, d_ffn, K):
     """Elements of the MoC+GCP stored set besides D: M, G.M and U.M kept compactly (Table 1)."""
     return 3 * s * K
+
+
+# ------------------------------------------------ MoC inside the experts of an MoE layer
+def moc_forward_experts(X, offsets, W_gate, W_up, W_down, K):
+    """Section "Compatibility with MoE architectures": every expert's MLP is a MoC feed-forward
+    network with its own weights.  X [A, d] holds the routed token copies sorted by expert; rows
+    offsets[e] .. offsets[e+1]-1 belong to expert e; W_* are lists (or stacked arrays) with one
+    matrix per expert in the paper's shapes.  Routing and the weighted combination of the experts'
+    outputs are the surrounding MoE layer's and not part of this function.
+    Returns (D, M, G, U) for all rows, in the order of X."""
+    X = _f64(X)
+    offsets = [int(o) for o in offsets]
+    if offsets[0] != 0 or offsets[-1] != X.shape[0] or any(b < a for a, b in zip(offsets, offsets[1:])):
+        raise ValueError("offsets must ascend from 0 to the number of rows")
+    F = np.asarray(W_gate[0]).shape[1]
+    D = np.zeros((X.shape[0], np.asarray(W_down[0]).shape[1]), dtype=F64)
+    M = np.zeros((X.shape[0], F), dtype=bool)
+    G = np.zeros((X.shape[0], F), dtype=F64)
+    U = np.zeros((X.shape[0], F), dtype=F64)
+    for e in range(len(offsets) - 1):
+        lo, hi = offsets[e], offsets[e + 1]
+        if hi > lo:
+            D[lo:hi], M[lo:hi], G[lo:hi], U[lo:hi] = moc_forward(X[lo:hi], W_gate[e], W_up[e], W_down[e], K)
+    return D, M, G, U
+
+
+def moc_backward_experts(X, offsets, W_gate, W_up, W_down, M, GM, UM, dD):
+    """Backward of moc_forward_experts: Eqs. (bp-1)...(bp-5) expert by expert.  Returns dX [A, d] and
+    per-expert lists dW_gate, dW_up, dW_down (zero for an expert without rows)."""
+    X, dD = _f64(X), _f64(dD)
+    offsets = [int(o) for o in offsets]
+    dX = np.zeros_like(X)
+    dWg, dWu, dWd = [], [], []
+    for e in range(len(offsets) - 1):
+        lo, hi = offsets[e], offsets[e + 1]
+        Wg, Wu, Wd = _f64(W_gate[e]), _f64(W_up[e]), _f64(W_down[e])
+        if hi > lo:
+            dx, dg, du, dd = moc_backward(X[lo:hi], Wg, Wu, Wd, M[lo:hi], GM[lo:hi], UM[lo:hi], dD[lo:hi])
+            dX[lo:hi] = dx
+        else:
+            dg, du, dd = np.zeros_like(Wg), np.zeros_like(Wu), np.zeros_like(Wd)
+        dWg.append(dg)
+        dWu.append(du)
+        dWd.append(dd)
+    return dX, dWg, dWu, dWd
 
 
 # ----------------------------------------------------------- RMSNorm, residual, the stack

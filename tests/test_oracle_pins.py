@@ -400,3 +400,106 @@ def test_keyed_masks_against_library_routines_and_monotonicity():
     np.testing.assert_array_equal(D, O.moc_forward_given_mask(X, Wg, Wu, Wd, M)[0])
     np.testing.assert_array_equal(M, O.topk_mask_keyed(Gm, 9, "abs_silu"))
     np.testing.assert_array_equal(O.moc_forward_keyed(X, Wg, Wu, Wd, 9, "gate")[0], O.moc_forward(X, Wg, Wu, Wd, 9)[0])
+
+
+# ------------------------------------------------------------- MoC inside MoE experts
+def _rand_experts(seed, E, d, F, scale=0.3):
+    rng = np.random.default_rng(seed)
+    return ([rng.standard_normal((d, F)) * scale for _ in range(E)], [rng.standard_normal((d, F)) * scale for _ in range(E)],
+            [rng.standard_normal((F, d)) * scale for _ in range(E)])
+
+
+def test_experts_reduce_to_the_plain_layer_and_to_single_rows():
+    rng = np.random.default_rng(50)
+    E, d, F, K = 3, 5, 12, 4
+    Wg, Wu, Wd = _rand_experts(51, E, d, F)
+    X = rng.standard_normal((11, d))
+    offsets = [0, 4, 4, 11]                                 # the second expert gets no rows
+    D, M, G, U = O.moc_forward_experts(X, offsets, Wg, Wu, Wd, K)
+    # one expert holding every row is the plain layer
+    D1, M1, _, _ = O.moc_forward_experts(X, [0, 11], Wg[:1], Wu[:1], Wd[:1], K)
+    D0, M0, _, _ = O.moc_forward(X, Wg[0], Wu[0], Wd[0], K)
+    np.testing.assert_array_equal(D1, D0)
+    np.testing.assert_array_equal(M1, M0)
+    # every row is what the decode recipe gives for that row with its expert's weights
+    for t in range(11):
+        e = 0 if t < 4 else 2
+        dvec, C = O.moc_decode(X[t], Wg[e], Wu[e], Wd[e], K)
+        np.testing.assert_allclose(D[t], dvec, rtol=1e-12, atol=1e-14)
+        assert list(np.flatnonzero(M[t])) == C.tolist()
+    with pytest.raises(ValueError):
+        O.moc_forward_experts(X, [0, 5, 3, 11], Wg, Wu, Wd, K)
+
+
+def test_experts_dense_limit_is_a_mixtral_style_layer_in_torch():
+    # K = d_ffn, top-2 of 4 experts, softmax weights over the two: written independently with torch ops
+    rng = np.random.default_rng(52)
+    E, d, F, T = 4, 6, 10, 9
+    Wg, Wu, Wd = _rand_experts(53, E, d, F)
+    Xtok = rng.standard_normal((T, d))
+    router = rng.standard_normal((d, E))
+    logits = torch.tensor(Xtok @ router)
+    top = torch.topk(logits, 2, dim=1)
+    wts = torch.softmax(top.values, dim=1).numpy()
+    experts = top.indices.numpy()
+    # torch reference: dense SwiGLU experts, weighted sum
+    ref = np.zeros((T, d))
+    for t in range(T):
+        for s in range(2):
+            e = experts[t, s]
+            xt = torch.tensor(Xtok[t])
+            h = torch.nn.functional.silu(xt @ torch.tensor(Wg[e])) * (xt @ torch.tensor(Wu[e]))
+            ref[t] += wts[t, s] * (h @ torch.tensor(Wd[e])).numpy()
+    # oracle path: sort the 2T routed copies by expert, run the expert form, combine
+    pairs = sorted((int(experts[t, s]), t, s) for t in range(T) for s in range(2))
+    offsets = [0] + [sum(1 for p in pairs if p[0] <= e) for e in range(E)]
+    Xs = np.stack([Xtok[t] for _, t, _ in pairs])
+    D, M, _, _ = O.moc_forward_experts(Xs, offsets, Wg, Wu, Wd, F)
+    assert M.all()
+    got = np.zeros((T, d))
+    for row, (_, t, s) in enumerate(pairs):
+        got[t] += wts[t, s] * D[row]
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_experts_backward_finite_differences():
+    rng = np.random.default_rng(54)
+    E, d, F, K = 2, 4, 8, 3
+    Wg, Wu, Wd = _rand_experts(55, E, d, F, scale=0.7)
+    X = rng.standard_normal((6, d))
+    offsets = [0, 2, 6]
+    dD = rng.standard_normal((6, d))
+    D, M, G, U = O.moc_forward_experts(X, offsets, Wg, Wu, Wd, K)
+    dX, dWg, dWu, dWd = O.moc_backward_experts(X, offsets, Wg, Wu, Wd, M, G * M, U * M, dD)
+
+    def loss(Xv, Wgv, Wuv, Wdv):
+        out = np.zeros_like(D)
+        for e in range(E):
+            lo, hi = offsets[e], offsets[e + 1]
+            out[lo:hi] = O.moc_forward_given_mask(Xv[lo:hi], Wgv[e], Wuv[e], Wdv[e], M[lo:hi])[0]
+        return float((out * dD).sum())
+
+    h = 1e-6
+    for (t, c) in ((0, 1), (3, 2), (5, 0)):
+        Xp, Xm = X.copy(), X.copy()
+        Xp[t, c] += h
+        Xm[t, c] -= h
+        assert abs((loss(Xp, Wg, Wu, Wd) - loss(Xm, Wg, Wu, Wd)) / (2 * h) - dX[t, c]) < 1e-6
+    for e, (r, c) in ((0, (1, 5)), (1, (3, 2))):
+        for which, grad in ((0, dWg), (1, dWu)):
+            Wp = [w.copy() for w in (Wg if which == 0 else Wu)]
+            Wm = [w.copy() for w in (Wg if which == 0 else Wu)]
+            Wp[e][r, c] += h
+            Wm[e][r, c] -= h
+            lp = loss(X, Wp, Wu, Wd) if which == 0 else loss(X, Wg, Wp, Wd)
+            lm = loss(X, Wm, Wu, Wd) if which == 0 else loss(X, Wg, Wm, Wd)
+            assert abs((lp - lm) / (2 * h) - grad[e][r, c]) < 1e-6
+        Wp = [w.copy() for w in Wd]
+        Wm = [w.copy() for w in Wd]
+        Wp[e][c, r] += h
+        Wm[e][c, r] -= h
+        assert abs((loss(X, Wg, Wu, Wp) - loss(X, Wg, Wu, Wm)) / (2 * h) - dWd[e][c, r]) < 1e-6
+    # an expert without rows has zero weight gradients
+    _, M1, G1, U1 = O.moc_forward_experts(X, [0, 6, 6], Wg, Wu, Wd, K)
+    _, g0, _, d0 = O.moc_backward_experts(X, [0, 6, 6], Wg, Wu, Wd, M1, G1 * M1, U1 * M1, dD)
+    assert not g0[1].any() and not d0[1].any()
