@@ -135,6 +135,26 @@ moc_status moc_topk_rows_keyed(int32_t T, int32_t F, int32_t K, int32_t key_mode
                                int64_t ldg, float* key_scratch, int32_t* idx, float* gsel,
                                void* hip_stream);
 
+/* MoC as the MLP of every expert of an MoE layer (section "Compatibility with MoE architectures").
+ * The rows of x are the routed token copies, sorted by expert: rows expert_offsets[e] ..
+ * expert_offsets[e+1]-1 belong to expert e (HOST array of n_experts + 1 ascending int32, first 0,
+ * last shape->T; an expert may have no rows).  wg, wu, wd and their gradients hold the experts'
+ * channel-major matrices one after the other, [n_experts, F, d].  Routing and the weighted
+ * combination of the experts' outputs belong to the surrounding MoE layer and are the caller's.
+ * Everything else -- outputs, stored set, workspace (MOC_OP_FWD / MOC_OP_BWD for shape) -- as
+ * moc_ffn_fwd / moc_ffn_bwd; each projection runs as one launch over all experts.  Weight
+ * gradients of an expert without rows are set to zero.  n_experts <= 8. */
+moc_status moc_ffn_fwd_experts(const moc_shape* shape, int32_t n_experts, const int32_t* expert_offsets,
+                               const void* x, const void* wg, const void* wu, const void* wd, void* y,
+                               int32_t* idx, void* gvals, void* uvals,
+                               void* ws, size_t ws_bytes, void* hip_stream);
+
+moc_status moc_ffn_bwd_experts(const moc_shape* shape, int32_t n_experts, const int32_t* expert_offsets,
+                               const void* x, const void* wg, const void* wu, const void* wd,
+                               const int32_t* idx, const void* gvals, const void* uvals, const void* dy,
+                               void* dx, void* dwg, void* dwu, void* dwd,
+                               void* ws, size_t ws_bytes, void* hip_stream);
+
 /* MoC_{a:b}, the grouped Top-K variant (item "MoC with structured 2:8 sparsity" of section
  * "Mixture-of-Channels architecture"; a:b defined before Theorem 1): the mask keeps the a largest
  * signed gate values of every contiguous group of b channels (channels q*b .. q*b+b-1), ties to

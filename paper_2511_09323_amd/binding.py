@@ -18,7 +18,7 @@ OP_FWD, OP_BWD, OP_DECODE, OP_SWIGLU_FWD, OP_SWIGLU_BWD = range(5)
 
 EXPORTS = (
     "moc_workspace_bytes", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
-    "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_keyed", "moc_ffn_decode_keyed", "moc_topk_rows_keyed", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
+    "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_experts", "moc_ffn_bwd_experts", "moc_ffn_fwd_keyed", "moc_ffn_decode_keyed", "moc_topk_rows_keyed", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
     "moc_timing_collect", "moc_timing_get", "moc_timing_reset", "moc_status_string",
     "moc_last_error", "moc_version",
 )
@@ -62,6 +62,10 @@ def load_library():
     lib.moc_swiglu_bwd.argtypes = [shp] + [vp] * 12 + [sz, vp]
     lib.moc_topk_rows.restype = ctypes.c_int
     lib.moc_topk_rows.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp]
+    lib.moc_ffn_fwd_experts.restype = ctypes.c_int
+    lib.moc_ffn_fwd_experts.argtypes = [shp, i32, ctypes.POINTER(i32)] + [vp] * 9 + [sz, vp]
+    lib.moc_ffn_bwd_experts.restype = ctypes.c_int
+    lib.moc_ffn_bwd_experts.argtypes = [shp, i32, ctypes.POINTER(i32)] + [vp] * 13 + [sz, vp]
     lib.moc_ffn_fwd_keyed.restype = ctypes.c_int
     lib.moc_ffn_fwd_keyed.argtypes = [shp, i32] + [vp] * 9 + [sz, vp]
     lib.moc_ffn_decode_keyed.restype = ctypes.c_int
@@ -277,6 +281,68 @@ def moc_topk_rows(g, K):
     gsel = torch.empty((T, K), dtype=torch.float32, device=g.device)
     _check(lib.moc_topk_rows(T, F, K, ctypes.c_void_p(g.data_ptr()), ldg, _ptr(idx), _ptr(gsel), _stream()))
     return idx, gsel
+
+
+def _offsets(offsets):
+    arr = (ctypes.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    return arr, len(offsets) - 1
+
+
+def moc_ffn_fwd_experts(x, offsets, wg, wu, wd, K, ws=None, out=None):
+    """MoC as the MLP of MoE experts.  x [A,d]: routed rows sorted by expert; offsets: n_experts + 1 host
+    integers; wg, wu, wd [n_experts, F, d].  Returns (y, idx, gvals, uvals) for all rows."""
+    lib = load_library()
+    T, d = x.shape
+    E, F = wg.shape[0], wg.shape[1]
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((T, d), dtype=dt, device=x.device)
+        idx = torch.empty((T, K), dtype=torch.int32, device=x.device)
+        gvals = torch.empty((T, K), dtype=dt, device=x.device)
+        uvals = torch.empty((T, K), dtype=dt, device=x.device)
+    else:
+        y, idx, gvals, uvals = out
+    ws, ws_bytes = _workspace(ws, T, d, F, K, dt, OP_FWD, x.device)
+    shp = _shape(T, d, F, K, code)
+    off, n = _offsets(offsets)
+    if n != E:
+        raise MocError("MOC_ERR_BAD_ARG", "offsets must have n_experts + 1 entries")
+    _check(lib.moc_ffn_fwd_experts(ctypes.byref(shp), n, off, _ptr(x, dt, (T, d), "x"), _ptr(wg, dt, (E, F, d), "wg"),
+                                   _ptr(wu, dt, (E, F, d), "wu"), _ptr(wd, dt, (E, F, d), "wd"), _ptr(y, dt, (T, d), "y"),
+                                   _ptr(idx, torch.int32, (T, K), "idx"), _ptr(gvals, dt, (T, K), "gvals"),
+                                   _ptr(uvals, dt, (T, K), "uvals"), _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return y, idx, gvals, uvals
+
+
+def moc_ffn_bwd_experts(x, offsets, wg, wu, wd, idx, gvals, uvals, dy, ws=None, out=None):
+    """Backward of moc_ffn_fwd_experts.  Returns (dx [A,d], dwg, dwu, dwd [n_experts, F, d])."""
+    lib = load_library()
+    T, d = x.shape
+    E, F = wg.shape[0], wg.shape[1]
+    K = idx.shape[1]
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        dx = torch.empty((T, d), dtype=dt, device=x.device)
+        dwg = torch.empty((E, F, d), dtype=dt, device=x.device)
+        dwu = torch.empty((E, F, d), dtype=dt, device=x.device)
+        dwd = torch.empty((E, F, d), dtype=dt, device=x.device)
+    else:
+        dx, dwg, dwu, dwd = out
+    ws, ws_bytes = _workspace(ws, T, d, F, K, dt, OP_BWD, x.device)
+    shp = _shape(T, d, F, K, code)
+    off, n = _offsets(offsets)
+    if n != E:
+        raise MocError("MOC_ERR_BAD_ARG", "offsets must have n_experts + 1 entries")
+    _check(lib.moc_ffn_bwd_experts(ctypes.byref(shp), n, off, _ptr(x, dt, (T, d), "x"), _ptr(wg, dt, (E, F, d), "wg"),
+                                   _ptr(wu, dt, (E, F, d), "wu"), _ptr(wd, dt, (E, F, d), "wd"),
+                                   _ptr(idx, torch.int32, (T, K), "idx"), _ptr(gvals, dt, (T, K), "gvals"),
+                                   _ptr(uvals, dt, (T, K), "uvals"), _ptr(dy, dt, (T, d), "dy"),
+                                   _ptr(dx, dt, (T, d), "dx"), _ptr(dwg, dt, (E, F, d), "dwg"),
+                                   _ptr(dwu, dt, (E, F, d), "dwu"), _ptr(dwd, dt, (E, F, d), "dwd"),
+                                   _ptr(ws, name="ws"), ws_bytes, _stream()))
+    return dx, dwg, dwu, dwd
 
 
 KEY_MODES = {"gate": 0, "silu": 1, "abs_silu": 2}

@@ -379,6 +379,26 @@ __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatc
     gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], item - z * nblk);
 }
 
+// Up to NB independent problems that share the output width, the contraction lengths and the layouts
+// but not the number of rows (one product per expert of an MoE layer, or the weight-gradient products
+// of all experts, whose contraction runs over each expert's own rows) in one launch.  cum[z] is the
+// number of tiles before problem z; the work items are the tiles of all problems, problem after
+// problem, dealt to the XCDs as contiguous ranges.
+template <class Epi, int NB> struct MfmaGroup {
+    MfmaProblem pr[NB];
+    Epi epi[NB];
+    int cum[NB + 1];
+};
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_group_kernel(MfmaGroup<Epi, NB> g, int nprob, int tiles_n) {
+    const int item = xcd_contiguous_index(blockIdx.x, g.cum[nprob]);
+    int z = 0;
+    while (z + 1 < nprob && item >= g.cum[z + 1]) ++z;
+    const int tiles_m = (g.cum[z + 1] - g.cum[z]) / tiles_n;
+    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(g.pr[z], tiles_m, tiles_n, g.epi[z], item - g.cum[z]);
+}
+
 // Two independent problems of one shape and layout with different epilogues in one launch (gate and
 // up projection of the forward): the work items are the tiles of the first problem, then of the second.
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class EpiA, class EpiB, int NWV = 4, int NSETS = 2>
@@ -438,6 +458,27 @@ inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipSt
     }
     const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(NB * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// Fills g.cum from the problems' row counts (problems with M = 0 get no tiles) and launches.
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+inline hipError_t launch_gemm_bf16_mfma_group(MfmaGroup<Epi, NB>& g, int nprob, hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_group_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_n = (g.pr[0].N + BN - 1) / BN;
+    g.cum[0] = 0;
+    for (int z = 0; z < nprob; ++z) g.cum[z + 1] = g.cum[z] + (g.pr[z].M + BM - 1) / BM * tiles_n;
+    for (int z = nprob; z < NB; ++z) g.cum[z + 1] = g.cum[nprob];
+    if (g.cum[nprob] == 0) return hipSuccess;
+    hipLaunchKernelGGL(kern, dim3(g.cum[nprob]), dim3(NWV * 64), Cfg::kLds, st, g, nprob, tiles_n);
     return hipGetLastError();
 }
 

@@ -276,6 +276,61 @@ moc_status run_gemm_pair(const char* name, const char* name_a, const char* name_
     return run_gemm<E, false, false>(name_b, pb, eb, st);
 }
 
+// Up to NB products that differ only in their row counts (and, for weight gradients, in their
+// contraction lengths) in one launch: one per expert of an MoE layer.  Problems with M = 0 are
+// skipped.  Falls back to one run_gemm per problem when the MFMA kernel cannot take all of them.
+template <class E, bool AKM, bool BKM, class Epi, int NB>
+moc_status run_gemm_grouped(const char* name, int nprob, const GemmProblem<E>* pr, const Epi* epi, hipStream_t st) {
+    if constexpr (std::is_same<E, bf16_t>::value) {
+        bool ok = !options().force_generic && nprob <= NB;
+        bool tail = false, padded = true;
+        int64_t total_m = 0;
+        for (int z = 0; z < nprob && ok; ++z) {
+            if (pr[z].M == 0) continue;
+            ok = mfma_problem_ok(pr[z]) && pr[z].N == pr[0].N && (pr[z].Kc2 == 0) == (pr[0].Kc2 == 0);
+            tail = tail || pr[z].Kc % kMfmaBK != 0 || pr[z].Kc2 % kMfmaBK != 0;
+            const GemmOperand<bf16_t>& kc = AKM ? pr[z].B : pr[z].A;
+            padded = padded && pr[z].kc_zero_padded && kc.ld >= round_up(std::max(pr[z].Kc, pr[z].Kc2), kMfmaBK);
+            total_m += pr[z].M;
+        }
+        if (ok && total_m > 0) {
+            struct Cand { int bm, bn; double penalty; };
+            static const Cand cands[3] = {{256, 256, 1.0}, {256, 192, 1.15}, {128, 128, 1.6}};
+            int best = 0;
+            double best_cost = 0.0;
+            for (int c = 0; c < 3; ++c) {
+                int64_t tiles = 0;
+                for (int z = 0; z < nprob; ++z)
+                    tiles += (int64_t)((pr[z].M + cands[c].bm - 1) / cands[c].bm) * ((pr[0].N + cands[c].bn - 1) / cands[c].bn);
+                const double cost = (double)((tiles + 255) / 256) * cands[c].bm * cands[c].bn * cands[c].penalty;
+                if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
+            }
+            if (options().tile == 256) best = 0;
+            if (options().tile == 192) best = 1;
+            if (options().tile == 128) best = 2;
+            MfmaGroup<Epi, NB> g;
+            for (int z = 0; z < nprob; ++z) { g.pr[z] = pr[z]; g.epi[z] = epi[z]; }
+            const int mode = !tail ? 0 : ((AKM != BKM && padded) ? 2 : 1);
+            Span span(name, st);
+            hipError_t e = hipSuccess;
+#define MOC_GROUP_LAUNCH(BM_, BN_)                                                                                          \
+    (mode == 0   ? launch_gemm_bf16_mfma_group<BM_, BN_, AKM, BKM, 0, Epi, NB, 4, 3>(g, nprob, st)                            \
+     : mode == 2 ? launch_gemm_bf16_mfma_group<BM_, BN_, AKM, BKM, (AKM != BKM ? 2 : 1), Epi, NB, 4, 3>(g, nprob, st)        \
+                 : launch_gemm_bf16_mfma_group<BM_, BN_, AKM, BKM, 1, Epi, NB, 4, 3>(g, nprob, st))
+            e = best == 0 ? MOC_GROUP_LAUNCH(256, 256) : best == 1 ? MOC_GROUP_LAUNCH(256, 192) : MOC_GROUP_LAUNCH(128, 128);
+#undef MOC_GROUP_LAUNCH
+            if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+            return MOC_OK;
+        }
+    }
+    for (int z = 0; z < nprob; ++z) {
+        if (pr[z].M == 0) continue;
+        moc_status s = run_gemm<E, AKM, BKM>(name, pr[z], epi[z], st);
+        if (s != MOC_OK) return s;
+    }
+    return MOC_OK;
+}
+
 // LDS-resident Top-K: any row length up to the LDS capacity, any alignment.
 template <class E, int NT, int VEC, bool FUSED>
 moc_status run_topk_lds(const char* name, const TopkArgs<E>& a, int T, hipStream_t st) {
@@ -536,6 +591,113 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
     GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F, true};
     return run_gemm<E, false, true>("gemm_dx", px, EpiStore<E>{dx, D.d, D.d, 0}, st);
+}
+
+// ------------------------------------------------------------ MoC inside MoE experts
+constexpr int kMaxExperts = 8;
+
+// Forward for rows already routed and sorted by expert (paper section "Compatibility with MoE
+// architectures": every expert's MLP is a MoC network): rows off[e] .. off[e+1]-1 use the weights of
+// expert e.  The three projections run as one grouped launch each over the experts; the row Top-K
+// is expert-agnostic and runs once over all rows.
+template <class E>
+moc_status fwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const E* x, const E* wg, const E* wu, const E* wd,
+                            E* y, int32_t* idx, E* gvals, E* uvals, void* ws, hipStream_t st) {
+    FwdWs<E> W(ws, D, false);
+    const int64_t wsz = (int64_t)D.F * D.d;
+    GemmProblem<E> pr[kMaxExperts];
+    EpiStore<float> eg[kMaxExperts];
+    EpiStore<E> ee[kMaxExperts];
+    moc_status s;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        pr[e] = GemmProblem<E>{kc_operand<E>(x + r0 * D.d, D.d), kc_operand<E>(wg + e * wsz, D.d), off[e + 1] - off[e], D.F, D.d, 0, false};
+        eg[e] = EpiStore<float>{W.G + r0 * D.ldF, D.ldF, D.F, 0};
+    }
+    if ((s = run_gemm_grouped<E, false, false, EpiStore<float>, kMaxExperts>("gemm_gate_experts", n_exp, pr, eg, st)) != MOC_OK) return s;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        pr[e].B = kc_operand<E>(wu + e * wsz, D.d);
+        ee[e] = EpiStore<E>{W.U + r0 * D.ldF, D.ldF, D.F, 0};
+    }
+    if ((s = run_gemm_grouped<E, false, false, EpiStore<E>, kMaxExperts>("gemm_up_experts", n_exp, pr, ee, st)) != MOC_OK) return s;
+    TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF, nullptr};
+    s = D.ldF > 6144 ? run_topk<E, 512, true>("topk_select_act", a, D.T, st) : run_topk<E, 256, true>("topk_select_act", a, D.T, st);
+    if (s != MOC_OK) return s;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        pr[e] = GemmProblem<E>{kc_operand<E>(W.Zd + r0 * D.ldF, D.ldF), km_operand<E>(wd + e * wsz, D.d, D.d), off[e + 1] - off[e], D.d, D.F, 0, true};
+        ee[e] = EpiStore<E>{y + r0 * D.d, D.d, D.d, 0};
+    }
+    return run_gemm_grouped<E, false, true, EpiStore<E>, kMaxExperts>("gemm_down_experts", n_exp, pr, ee, st);
+}
+
+template <class E> __global__ void fill_zero_kernel(E* p, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = E(0);
+}
+
+// Backward of fwd_experts_impl: dZ' and dX as grouped launches over the experts, the pointwise step
+// once over all rows, and the 3 x n_exp weight-gradient products (each contracting over its expert's
+// own rows) as one grouped launch.  An expert without rows gets zero weight gradients.
+template <class E>
+moc_status bwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const E* x, const E* wg, const E* wu, const E* wd,
+                            const int32_t* idx, const E* gvals, const E* uvals, const E* dy, E* dx, E* dwg, E* dwu, E* dwd,
+                            void* ws, hipStream_t st) {
+    BwdWs<E> W(ws, D, false);
+    const int64_t wsz = (int64_t)D.F * D.d;
+    const size_t expand_lds = (size_t)3 * D.ldF * sizeof(E);
+    if (expand_lds > 160 * 1024 - 64) return fail(MOC_ERR_UNSUPPORTED, "F = %d too large for the expert backward", D.F);
+    GemmProblem<E> pr[3 * kMaxExperts];
+    EpiStore<E> ee[3 * kMaxExperts];
+    moc_status s;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        pr[e] = GemmProblem<E>{kc_operand<E>(dy + r0 * D.d, D.d), kc_operand<E>(wd + e * wsz, D.d), off[e + 1] - off[e], D.F, D.d, 0, false};
+        ee[e] = EpiStore<E>{W.dZd + r0 * D.ldF, D.ldF, D.F, 0};
+    }
+    if ((s = run_gemm_grouped<E, false, false, EpiStore<E>, kMaxExperts>("gemm_dz_experts", n_exp, pr, ee, st)) != MOC_OK) return s;
+    {
+        auto kern = bwd_expand_kernel<E>;
+        static bool attr = false;
+        if (!attr) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        160 * 1024 - 64));
+            attr = true;
+        }
+        Span span("bwd_pointwise_expand", st);
+        hipLaunchKernelGGL(kern, dim3(D.T), dim3(256), expand_lds, st, idx, gvals, uvals, W.dZd, D.K, D.F, (int64_t)D.ldF, W.Zd,
+                           W.dGd, W.dUd);
+        HIP_TRY(hipGetLastError());
+    }
+    int np = 0;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        const int rows = off[e + 1] - off[e];
+        if (rows == 0) {
+            Span span("zero_expert_grads", st);
+            for (E* p : {dwd + e * wsz, dwg + e * wsz, dwu + e * wsz})
+                hipLaunchKernelGGL((fill_zero_kernel<E>), dim3(1024), dim3(256), 0, st, p, wsz);
+            HIP_TRY(hipGetLastError());
+            continue;
+        }
+        const E* ops[3] = {W.Zd, W.dGd, W.dUd};
+        const E* rhs[3] = {dy, x, x};
+        E* outs[3] = {dwd, dwg, dwu};
+        for (int k = 0; k < 3; ++k) {
+            pr[np] = GemmProblem<E>{km_operand<E>(ops[k] + r0 * D.ldF, D.ldF, D.ldF), km_operand<E>(rhs[k] + r0 * D.d, D.d, D.d),
+                                    D.F, D.d, rows, 0, false};
+            ee[np] = EpiStore<E>{outs[k] + e * wsz, D.d, D.d, 0};
+            ++np;
+        }
+    }
+    if ((s = run_gemm_grouped<E, true, true, EpiStore<E>, 3 * kMaxExperts>("gemm_dw_experts", np, pr, ee, st)) != MOC_OK) return s;
+    for (int e = 0; e < n_exp; ++e) {
+        const int64_t r0 = off[e];
+        pr[e] = GemmProblem<E>{kc_operand<E>(W.dGd + r0 * D.ldF, D.ldF, W.dUd + r0 * D.ldF),
+                               km_operand<E>(wg + e * wsz, D.d, D.d, wu + e * wsz), off[e + 1] - off[e], D.d, D.F, D.F, true};
+        ee[e] = EpiStore<E>{dx + r0 * D.d, D.d, D.d, 0};
+    }
+    return run_gemm_grouped<E, false, true, EpiStore<E>, kMaxExperts>("gemm_dx_experts", n_exp, pr, ee, st);
 }
 
 // ------------------------------------------------------------------------ dense SwiGLU
@@ -929,6 +1091,53 @@ moc_status moc_topk_rows_keyed(int32_t T, int32_t F, int32_t K, int32_t key_mode
         a.g_raw = g;
     }
     return run_topk<float, 256, false>("topk_rows", a, T, st);
+}
+
+static moc_status check_offsets(const moc_shape* shape, int32_t n_experts, const int32_t* off) {
+    if (n_experts < 1 || n_experts > kMaxExperts) return fail(MOC_ERR_UNSUPPORTED, "n_experts must be 1..%d (got %d)", kMaxExperts, n_experts);
+    if (!off) return fail(MOC_ERR_BAD_ARG, "expert_offsets is NULL");
+    if (off[0] != 0 || off[n_experts] != shape->T) return fail(MOC_ERR_BAD_ARG, "expert_offsets must run from 0 to T");
+    for (int e = 0; e < n_experts; ++e)
+        if (off[e + 1] < off[e]) return fail(MOC_ERR_BAD_ARG, "expert_offsets must ascend");
+    return MOC_OK;
+}
+
+moc_status moc_ffn_fwd_experts(const moc_shape* shape, int32_t n_experts, const int32_t* expert_offsets, const void* x,
+                               const void* wg, const void* wu, const void* wd, void* y, int32_t* idx, void* gvals,
+                               void* uvals, void* ws, size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    if ((s = check_offsets(shape, n_experts, expert_offsets)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_WS(MOC_OP_FWD);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return fwd_experts_impl<bf16_t>(D, n_experts, expert_offsets, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu,
+                                        (const bf16_t*)wd, (bf16_t*)y, idx, (bf16_t*)gvals, (bf16_t*)uvals, ws, st);
+    return fwd_experts_impl<float>(D, n_experts, expert_offsets, (const float*)x, (const float*)wg, (const float*)wu,
+                                   (const float*)wd, (float*)y, idx, (float*)gvals, (float*)uvals, ws, st);
+}
+
+moc_status moc_ffn_bwd_experts(const moc_shape* shape, int32_t n_experts, const int32_t* expert_offsets, const void* x,
+                               const void* wg, const void* wu, const void* wd, const int32_t* idx, const void* gvals,
+                               const void* uvals, const void* dy, void* dx, void* dwg, void* dwu, void* dwd, void* ws,
+                               size_t ws_bytes, void* hip_stream) {
+    moc_status s = check_shape(shape, false);
+    if (s != MOC_OK) return s;
+    if ((s = check_offsets(shape, n_experts, expert_offsets)) != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(idx); CHECK_PTR(gvals); CHECK_PTR(uvals);
+    CHECK_PTR(dy); CHECK_PTR(dx); CHECK_PTR(dwg); CHECK_PTR(dwu); CHECK_PTR(dwd);
+    CHECK_WS(MOC_OP_BWD);
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return bwd_experts_impl<bf16_t>(D, n_experts, expert_offsets, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu,
+                                        (const bf16_t*)wd, idx, (const bf16_t*)gvals, (const bf16_t*)uvals, (const bf16_t*)dy,
+                                        (bf16_t*)dx, (bf16_t*)dwg, (bf16_t*)dwu, (bf16_t*)dwd, ws, st);
+    return bwd_experts_impl<float>(D, n_experts, expert_offsets, (const float*)x, (const float*)wg, (const float*)wu,
+                                   (const float*)wd, idx, (const float*)gvals, (const float*)uvals, (const float*)dy, (float*)dx,
+                                   (float*)dwg, (float*)dwu, (float*)dwd, ws, st);
 }
 
 moc_status moc_ffn_fwd_grouped(const moc_shape* shape, int32_t ga, int32_t gb, const void* x, const void* wg,

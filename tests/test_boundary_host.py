@@ -96,6 +96,14 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moc_ffn_decode_keyed(ctypes.byref(s), -1, *([fake] * 7), 1 << 30, None) == -1
     assert lib.moc_topk_rows_keyed(4, 16, 4, 1, fake, 16, None, fake, fake, None) == -1            # keyed needs key_scratch
     assert _ws(lib, 4, 64, 128, 16, B.MOC_BF16, 5) > _ws(lib, 4, 64, 128, 16, B.MOC_BF16, B.OP_FWD)
+    # MoE experts: offsets are validated on the host
+    s = B.MocShape(50, 64, 128, 16, B.MOC_BF16)
+    off_ok = (ctypes.c_int32 * 3)(0, 20, 50)
+    off_bad = (ctypes.c_int32 * 3)(0, 60, 50)
+    assert lib.moc_ffn_fwd_experts(ctypes.byref(s), 2, off_bad, *([fake] * 9), 1 << 30, None) == -1
+    assert lib.moc_ffn_fwd_experts(ctypes.byref(s), 2, off_ok, *([fake] * 9), 16, None) == -2
+    assert lib.moc_ffn_fwd_experts(ctypes.byref(s), 9, off_ok, *([fake] * 9), 1 << 30, None) == -3
+    assert lib.moc_ffn_bwd_experts(ctypes.byref(s), 2, None, *([fake] * 13), 1 << 30, None) == -1
     # grouped Top-K (MoC_{a:b}): b in {4, 8, 16} dividing F, 1 <= a <= b, K = a F / b
     s = B.MocShape(4, 64, 128, 32, B.MOC_BF16)
     for a, b in ((2, 8), ):
