@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-grouped", action="store_true", help="skip the MoC 2:8 (grouped Top-K) legs")
+    ap.add_argument("--no-experts", action="store_true", help="skip the MoC-in-MoE-experts leg")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="run only moc_residual_add on 2 x 512 MiB (known traffic: 1 GiB read, 512 MiB written per "
@@ -214,6 +215,11 @@ def main():
                    "decode": decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, group=(2, 8)),
                    "decode_1of8": decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, group=(1, 8))}
 
+    # MoC inside MoE experts (the paper's Mixtral shapes: 8 experts, 2 per token)
+    experts = None
+    if not args.no_experts:
+        experts = [experts_leg(torch, moc, 512, 1376, 256, dev), experts_leg(torch, moc, 768, 2048, 384, dev)]
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
@@ -227,7 +233,7 @@ def main():
         "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
                    "T": T, "d_model": d, "d_ff": F, "K": K},
         "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
-        "decode": decode, "prefill_stack": stack, "grouped_2of8": grouped, "clocks_after_run": line_clocks,
+        "decode": decode, "prefill_stack": stack, "grouped_2of8": grouped, "moe_experts": experts, "clocks_after_run": line_clocks,
     }
     print(json.dumps(line))
 
@@ -297,6 +303,67 @@ def stack_leg(torch, moc, cfg, dev, layers=32):
                                      for k, m in (("gemm_gate", 1), ("gemm_up", 1), ("gemm_gate_up", 2), ("gemm_down", 1)) if k in kern},
             "rmsnorm_GBs": round(2 * row_bytes / (kern["rmsnorm"] * 1e-3) / 1e9, 1) if "rmsnorm" in kern else None,
             "residual_add_GBs": round(3 * row_bytes / (kern["residual_add"] * 1e-3) / 1e9, 1) if "residual_add" in kern else None}
+
+
+def experts_leg(torch, moc, d, F, K, dev, tokens=16384, n_exp=8, per_token=2):
+    """Forward + backward of MoC as the MLP of MoE experts on `tokens` tokens routed to `per_token` of
+    `n_exp` experts each (seeded, uneven split): one grouped launch per projection, against the same
+    work done with one moc_ffn_fwd / moc_ffn_bwd call per expert."""
+    bf = torch.bfloat16
+    A = tokens * per_token
+    rng = np.random.default_rng(60_000 + d)
+    counts = rng.multinomial(A, rng.dirichlet(np.full(n_exp, 8.0)))
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(60_000 + d)
+    x = torch.randn((A, d), generator=gen, device=dev, dtype=torch.float32).to(bf)
+    dy = torch.randn((A, d), generator=gen, device=dev, dtype=torch.float32).to(bf)
+    w = [(torch.randn((n_exp, F, d), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(bf) for _ in range(3)]
+    ws_f = torch.empty(moc.workspace_bytes(A, d, F, K, bf, 0), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(moc.workspace_bytes(A, d, F, K, bf, 1), dtype=torch.uint8, device=dev)
+    out_f = (torch.empty((A, d), dtype=bf, device=dev), torch.empty((A, K), dtype=torch.int32, device=dev),
+             torch.empty((A, K), dtype=bf, device=dev), torch.empty((A, K), dtype=bf, device=dev))
+    out_b = (torch.empty((A, d), dtype=bf, device=dev),) + tuple(torch.empty((n_exp, F, d), dtype=bf, device=dev) for _ in range(3))
+
+    def grouped():
+        y, idx, gv, uv = moc.moc_ffn_fwd_experts(x, offsets, w[0], w[1], w[2], K, ws=ws_f, out=out_f)
+        moc.moc_ffn_bwd_experts(x, offsets, w[0], w[1], w[2], idx, gv, uv, dy, ws=ws_b, out=out_b)
+
+    def looped():
+        for e in range(n_exp):
+            lo, hi = int(offsets[e]), int(offsets[e + 1])
+            if hi == lo:
+                continue
+            o_f = tuple(t[lo:hi] for t in out_f)
+            o_b = (out_b[0][lo:hi], out_b[1][e], out_b[2][e], out_b[3][e])
+            y, idx, gv, uv = moc.moc_ffn_fwd(x[lo:hi], w[0][e], w[1][e], w[2][e], K, ws=ws_f, out=o_f)
+            moc.moc_ffn_bwd(x[lo:hi], w[0][e], w[1][e], w[2][e], idx, gv, uv, dy[lo:hi], ws=ws_b, out=o_b)
+
+    res = {}
+    for name, fn in (("grouped", grouped), ("looped", looped)):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        n = 30
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) * 1e3 / n
+    moc.timing_reset()
+    moc.timing_enable(True)
+    for _ in range(10):
+        grouped()
+    torch.cuda.synchronize()
+    kern = {k: round(v / max(c, 1), 4) for k, (v, c) in moc.timing_read().items()}
+    moc.timing_enable(False)
+    moc.timing_reset()
+    executed = 18.0 * A * d * F            # dense-equivalent FLOPs of forward + backward over all routed rows
+    return {"workload": "MoC in MoE experts: %d tokens x %d of %d experts, d_model=%d d_ff=%d K=%d bf16, rows per expert %s" % (
+                tokens, per_token, n_exp, d, F, K, [int(c) for c in counts]),
+            "ms_per_step_grouped": round(res["grouped"], 4), "ms_per_step_one_call_per_expert": round(res["looped"], 4),
+            "tokens_per_s": round(tokens / (res["grouped"] * 1e-3), 1),
+            "executed_tflops": round(executed / (res["grouped"] * 1e-3) / 1e12, 1), "kernels_ms": kern}
 
 
 def grouped_train_leg(torch, moc, inputs, cfg, a, b, steps, warmup, dev):
