@@ -20,9 +20,14 @@
  *    (MOC_F32 or MOC_BF16).  All accumulation is fp32.  The Top-K decision is taken on the fp32
  *    gate accumulator before any rounding; equal values are ordered by channel, lower first,
  *    and -0.0 equals +0.0.  Non-finite inputs are not detected.
- *  - The library allocates no device memory and keeps no state between calls; scratch lives in
- *    the caller's workspace `ws` of at least moc_workspace_bytes(shape, op) bytes (256-byte
- *    aligned).  Two calls that overlap in time must not share a workspace.
+ *  - The library allocates no device memory; scratch lives in the caller's workspace `ws` of at
+ *    least moc_workspace_bytes(shape, op) bytes (256-byte aligned).  Two calls that overlap in
+ *    time must not share a workspace.  The only state kept between calls is a per-device set-up
+ *    done once, by moc_init() or by the first entry point called with that device current: the
+ *    dynamic-LDS limit of every kernel (hipFuncSetAttribute) and the device address of the static
+ *    scratch array.  It is guarded by a mutex and makes no stream operation, so a first call may be
+ *    made from any thread and under stream capture; a caller that wants the set-up outside its
+ *    capture or timing calls moc_init() beforehand.
  *  - Calls validate their arguments on the host, enqueue kernels on `hip_stream` (a hipStream_t,
  *    NULL = the default stream) and return without synchronising; outputs are valid in stream
  *    order.  Gradients are overwritten, not accumulated.
@@ -30,10 +35,10 @@
  *    text).  Argument errors are found before anything is launched and leave outputs untouched.
  *  - Limits: 1 <= K <= F <= 32768, T >= 1 (T <= 16 for decode), d >= 1; MOC_BF16 needs d % 8 == 0.
  *  - Environment variables for testing and tuning (none is needed in normal use):
- *    MOC_FORCE_GENERIC=1 (read once) sends every GEMM to the generic fp32-FMA kernel and decode to
- *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 (read once) forces an MFMA tile shape;
- *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n (read at every call) switch off, or set the
- *    workgroup count of, the single-launch grouped decode kernel.
+ *    MOC_FORCE_GENERIC=1 sends every GEMM to the generic fp32-FMA kernel and decode to
+ *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 forces an MFMA tile shape;
+ *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n switch off, or set the workgroup count of, the
+ *    single-launch grouped decode kernel.  All are read once, when the library is loaded.
  */
 #ifndef MOC_H
 #define MOC_H
@@ -77,6 +82,10 @@ typedef struct {
 
 /* Bytes of workspace `op` needs for `shape`; 0 if the shape is invalid. */
 size_t moc_workspace_bytes(const moc_shape* shape, int op);
+
+/* Per-device set-up for the device that is current (see the conventions above).  Optional: every
+ * entry point does the same on its first call on a device.  Returns MOC_ERR_HIP without a GPU. */
+moc_status moc_init(void);
 
 /* Training forward, Eqs. (MoC-1), (MoC-2).  Writes y[T,d] and the stored set idx[T,K] (int32),
  * gvals[T,K], uvals[T,K] (dtype).  Steps: gate projection (fp32), row Top-K, up projection,

@@ -17,7 +17,7 @@ MOC_F32, MOC_BF16 = 0, 1
 OP_FWD, OP_BWD, OP_DECODE, OP_SWIGLU_FWD, OP_SWIGLU_BWD = range(5)
 
 EXPORTS = (
-    "moc_workspace_bytes", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
+    "moc_workspace_bytes", "moc_init", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
     "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_experts", "moc_ffn_bwd_experts", "moc_ffn_fwd_keyed", "moc_ffn_decode_keyed", "moc_topk_rows_keyed", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
     "moc_timing_collect", "moc_timing_get", "moc_timing_reset", "moc_status_string",
     "moc_last_error", "moc_version",
@@ -50,6 +50,8 @@ def load_library():
     shp = ctypes.POINTER(MocShape)
     lib.moc_workspace_bytes.restype = sz
     lib.moc_workspace_bytes.argtypes = [shp, ctypes.c_int]
+    lib.moc_init.restype = ctypes.c_int
+    lib.moc_init.argtypes = []
     lib.moc_ffn_fwd.restype = ctypes.c_int
     lib.moc_ffn_fwd.argtypes = [shp] + [vp] * 9 + [sz, vp]
     lib.moc_ffn_bwd.restype = ctypes.c_int
@@ -134,6 +136,11 @@ def _stream():
 
 def _shape(T, d, F, K, code):
     return MocShape(int(T), int(d), int(F), int(K), int(code))
+
+
+def init():
+    """Per-device set-up for the current device (optional; every call does it on first use)."""
+    _check(load_library().moc_init())
 
 
 def workspace_bytes(T, d, F, K, dtype, op):

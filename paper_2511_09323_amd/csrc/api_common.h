@@ -1,0 +1,197 @@
+// Shared by the entry-point files of the library (moc_api.hip, moc_fwd.hip, moc_bwd.hip,
+// moc_decode.hip): error reporting, per-kernel timing spans, options from the environment, the
+// per-device set-up, argument checks and the workspace layouts.  Host code only.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/moc.h"
+#include "common.h"
+
+namespace mocapi {
+using namespace moc;
+
+// ------------------------------------------------------------------------------- errors
+extern thread_local char g_err[512];
+
+inline moc_status fail(moc_status s, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(MOC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---------------------------------------------------------------------- per-kernel timing
+// (state and bookkeeping live in moc_api.hip)
+extern bool g_timing_on;
+hipEvent_t timing_take_event();
+int timing_entry_index(const char* name);
+void timing_push(int entry, hipEvent_t start, hipEvent_t stop);
+
+// Brackets the launches made during its lifetime with two events on the stream.
+struct Span {
+    hipStream_t st;
+    hipEvent_t start = nullptr, stop = nullptr;
+    int entry = -1;
+    Span(const char* name, hipStream_t s) : st(s) {
+        if (!g_timing_on) return;
+        start = timing_take_event();
+        stop = timing_take_event();
+        if (!start || !stop) return;
+        entry = timing_entry_index(name);
+        (void)hipEventRecord(start, st);
+    }
+    ~Span() {
+        if (entry < 0) return;
+        (void)hipEventRecord(stop, st);
+        timing_push(entry, start, stop);
+    }
+};
+
+// ------------------------------------------------------------------------ small helpers
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+struct Carver {   // hands out 256-byte aligned pieces of the workspace
+    unsigned char* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    template <class T> T* take(size_t count) {
+        T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += round_up_sz(count * sizeof(T), 256);
+        return r;
+    }
+};
+
+struct Options {          // environment, read once when the library is loaded
+    int force_generic;    // MOC_FORCE_GENERIC=1: never use the MFMA GEMM
+    int tile;             // MOC_GEMM_TILE=256|192|128 forces a tile shape, 0 = choose by problem size
+    int decode_fused;     // MOC_DECODE_FUSED=0: grouped decode of one token as separate launches
+    int decode_fused_p;   // MOC_DECODE_FUSED_P=n: workgroups of the single-launch grouped decode kernel, 0 = choose
+    Options();
+};
+const Options& options();
+
+// Per-device set-up (kernel attributes); see moc_api.hip.
+moc_status ensure_init();
+
+#define MOC_SETUP()                                  \
+    do {                                             \
+        moc_status si_ = mocapi::ensure_init();      \
+        if (si_ != MOC_OK) return si_;               \
+    } while (0)
+
+moc_status check_shape(const moc_shape* s, bool decode);
+moc_status check_group(int F, int K, int ga, int gb);
+moc_status check_key_mode(int32_t key_mode);
+moc_status check_offsets(const moc_shape* shape, int32_t n_experts, const int32_t* off);
+
+#define CHECK_PTR(p)                                                                   \
+    do {                                                                               \
+        if ((p) == nullptr) return fail(MOC_ERR_BAD_ARG, "%s is NULL", #p);            \
+        if (!aligned16(p)) return fail(MOC_ERR_BAD_ARG, "%s is not 16-byte aligned", #p); \
+    } while (0)
+
+#define CHECK_WS(op)                                                                                  \
+    do {                                                                                              \
+        CHECK_PTR(ws);                                                                                \
+        size_t need_ = moc_workspace_bytes(shape, op);                                                \
+        if (ws_bytes < need_) return fail(MOC_ERR_WORKSPACE, "workspace: %zu bytes given, %zu needed", ws_bytes, need_); \
+    } while (0)
+
+// ------------------------------------------------------------------- workspace layouts
+struct Dims {
+    int T, d, F, K;
+    int ldF, nw;
+    explicit Dims(const moc_shape& s) : T(s.T), d(s.d), F(s.F), K(s.K) {
+        ldF = round_up(F, 64);
+        nw = ldF / 32;
+    }
+};
+
+template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gate, U, masked Z'
+    float *G, *keys;                   // keys: transformed selection keys (Top-K position variants only)
+    E *U, *Zd;
+    size_t bytes;
+    FwdWs(void* ws, const Dims& D, bool dense, bool keyed = false) {
+        Carver c(ws);
+        G = dense ? nullptr : c.take<float>((size_t)D.T * D.ldF);
+        U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
+        Zd = c.take<E>((size_t)D.T * D.ldF);
+        keys = keyed ? c.take<float>((size_t)D.T * D.ldF) : nullptr;
+        bytes = c.off;
+    }
+};
+
+template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mask of the fallback path)
+    uint32_t* maskw;
+    uint16_t* pref;
+    E *dZd, *Zd, *dGd, *dUd;
+    size_t bytes;
+    BwdWs(void* ws, const Dims& D, bool dense) {
+        Carver c(ws);
+        maskw = dense ? nullptr : c.take<uint32_t>((size_t)D.T * D.nw);
+        pref = dense ? nullptr : c.take<uint16_t>((size_t)D.T * D.nw);
+        dZd = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
+        Zd = c.take<E>((size_t)D.T * D.ldF);
+        dGd = c.take<E>((size_t)D.T * D.ldF);
+        dUd = c.take<E>((size_t)D.T * D.ldF);
+        bytes = c.off;
+    }
+};
+
+// Channel shares per token in the gather stage: shares x tokens fills the 256 CUs once (one
+// 512-thread workgroup per CU), and a multiple of 8 shares lets the kernel keep each share on one XCD.
+inline int decode_splits(int B, int K) {
+    const int by_batch = std::max(8, 256 / B / 8 * 8);
+    const int by_k = (K + 7) / 8;
+    return std::max(1, std::min(by_batch, by_k));
+}
+
+constexpr int kDecodeFusedMaxP = 512;
+
+struct DecodeWs {
+    float *g, *gkeys, *gsel, *z, *part;
+    int32_t* idx;
+    size_t bytes;
+    DecodeWs(void* ws, const Dims& D) {
+        Carver c(ws);
+        g = c.take<float>((size_t)D.T * D.ldF);
+        gkeys = c.take<float>((size_t)D.T * D.ldF);
+        gsel = c.take<float>((size_t)D.T * D.K);
+        z = c.take<float>((size_t)D.T * D.K);
+        idx = c.take<int32_t>((size_t)D.T * D.K);
+        // partial outputs: one per channel share, or one per workgroup of the single-launch grouped kernel
+        const int shares = std::max(decode_splits(D.T, D.K), D.T == 1 ? kDecodeFusedMaxP : 0);
+        part = c.take<float>((size_t)shares * D.T * D.d);
+        bytes = c.off;
+    }
+};
+
+template <class E> size_t workspace_for(const Dims& D, int op) {
+    switch (op) {
+        case MOC_OP_FWD: return FwdWs<E>(nullptr, D, false).bytes;
+        case MOC_OP_BWD: return BwdWs<E>(nullptr, D, false).bytes;
+        case MOC_OP_DECODE: return DecodeWs(nullptr, D).bytes;
+        case MOC_OP_SWIGLU_FWD: return FwdWs<E>(nullptr, D, true).bytes;
+        case MOC_OP_SWIGLU_BWD: return BwdWs<E>(nullptr, D, true).bytes;
+        case MOC_OP_FWD_KEYED: return FwdWs<E>(nullptr, D, false, true).bytes;
+    }
+    return 0;
+}
+
+
+constexpr int kMaxExperts = 8;
+
+}  // namespace mocapi

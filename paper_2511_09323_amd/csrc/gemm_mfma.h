@@ -34,6 +34,7 @@
 
 #include "common.h"
 #include "gemm_generic.h"
+#include "kernel_attrs.h"
 
 namespace moc {
 
@@ -42,23 +43,16 @@ typedef GemmProblem<bf16_t> MfmaProblem;
 constexpr int kMfmaBK = 32;
 constexpr int kMfmaStages = 3;
 
-#ifdef MOC_KC_PITCH80
-constexpr bool kKcSwizzle = false;
-#else
-constexpr bool kKcSwizzle = true;
-#endif
-
 // LDS byte offset of the 16-byte chunk `ch` (8 k) of row `row` in a k-contiguous tile: rows of 64
 // bytes, chunk position XORed with bits 2..3 of the row.  Both the staging writes (16 lanes = 4
 // rows x 4 chunks) and the fragment reads (16 lanes = 16 rows, one chunk) then hit 16 different
 // 16-byte bank groups.
 __device__ __forceinline__ int kc_lds_offset(int row, int ch) {
-    if (kKcSwizzle) return row * 64 + ((ch ^ ((row >> 2) & 3)) << 4);
-    return row * 80 + ch * 16;
+    return row * 64 + ((ch ^ ((row >> 2) & 3)) << 4);
 }
 
 template <int ROWS, bool KM> struct OperandTile {
-    static constexpr int kPitch = KM ? (ROWS * 2 + 64) : (kKcSwizzle ? kMfmaBK * 2 : kMfmaBK * 2 + 16);   // bytes
+    static constexpr int kPitch = KM ? (ROWS * 2 + 64) : kMfmaBK * 2;   // bytes
     static constexpr int kBytes = KM ? kMfmaBK * kPitch : ROWS * kPitch;
     static constexpr int kChunks64 = ROWS * kMfmaBK / 8 / 64;                   // 16-byte chunks per lane of one wavefront
 };
@@ -433,13 +427,7 @@ inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hi
     static_assert(NSETS >= 2 && NSETS <= 4, "two to four slices in flight");
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    LdsAttr<gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
     return hipGetLastError();
@@ -449,13 +437,7 @@ template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, i
 inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipStream_t st) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_batch_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    LdsAttr<gemm_bf16_mfma_batch_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(NB * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n);
     return hipGetLastError();
@@ -466,13 +448,7 @@ template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, i
 inline hipError_t launch_gemm_bf16_mfma_group(MfmaGroup<Epi, NB>& g, int nprob, hipStream_t st) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_group_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    LdsAttr<gemm_bf16_mfma_group_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_n = (g.pr[0].N + BN - 1) / BN;
     g.cum[0] = 0;
     for (int z = 0; z < nprob; ++z) g.cum[z + 1] = g.cum[z] + (g.pr[z].M + BM - 1) / BM * tiles_n;
@@ -487,13 +463,7 @@ inline hipError_t launch_gemm_bf16_mfma_pair(const MfmaProblem& pa, const EpiA& 
                                              hipStream_t st) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_pair_kernel<BM, BN, AKM, BKM, TAILMODE, EpiA, EpiB, NWV, NSETS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    LdsAttr<gemm_bf16_mfma_pair_kernel<BM, BN, AKM, BKM, TAILMODE, EpiA, EpiB, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_m = (pa.M + BM - 1) / BM, tiles_n = (pa.N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(2 * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, pa, ea, pb, eb, tiles_m, tiles_n);
     return hipGetLastError();

@@ -8,7 +8,7 @@ namespace moc {
 // From idx[T, K] (ascending per row) build the selection bit mask maskw[T, nw] (bit j % 32 of word
 // j / 32) and pref[T, nw], the number of selected channels before each word.  One workgroup per
 // row.  Entries of idx outside [0, F) are ignored.
-__global__ __launch_bounds__(256) void build_mask_kernel(const int32_t* __restrict__ idx, int K, int F, int nw,
+static __global__ __launch_bounds__(256) void build_mask_kernel(const int32_t* __restrict__ idx, int K, int F, int nw,
                                                          uint32_t* __restrict__ maskw, uint16_t* __restrict__ pref) {
     extern __shared__ uint32_t mask_smem[];   // nw words + 4 ints
     uint32_t* words = mask_smem;

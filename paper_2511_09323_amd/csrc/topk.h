@@ -49,7 +49,7 @@ template <class E> struct TopkArgs {
 
 // Selection keys of the Top-K position variants: mode 1 ranks SiLU(g) (ablation row "After SiLU"),
 // mode 2 ranks |SiLU(g)| (the selection of the proof of Theorem 1).  Element-wise, [T, ld] fp32.
-__global__ void topk_key_transform_kernel(const float* __restrict__ g, float* __restrict__ keys, int64_t n, int mode) {
+static __global__ void topk_key_transform_kernel(const float* __restrict__ g, float* __restrict__ keys, int64_t n, int mode) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const float s = silu_f32(g[i]);
         keys[i] = mode == 2 ? fabsf(s) : s;

@@ -318,10 +318,8 @@ def test_forward_backward_and_decode_replay_from_a_graph():
         moc.moc_ffn_bwd(x, Gd["wg"], Gd["wu"], Gd["wd"], idx, gv, uv, dy, ws=ws_b, out=out_b)
         moc.moc_ffn_decode(xd, Gd["wg"], Gd["wu"], Gd["wd"], K, ws=ws_d, out=out_d)
 
-    side = torch.cuda.Stream()
-    with torch.cuda.stream(side):
-        run()                                   # first calls set kernel attributes: outside the capture
-    torch.cuda.synchronize()
+    # no warm-up call: the library's per-device set-up makes no stream operation, so even the first
+    # call of a process may be captured
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         run()
