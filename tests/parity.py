@@ -32,8 +32,18 @@ def maxrel(a, b):
     return float(np.max(np.abs(a - b)) / (den if den > 0 else 1.0))
 
 
+def frobrel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / (den if den > 0 else 1.0))
+
+
 def assert_close(name, got, want, tol):
+    """The bar is the max-norm relative error per tensor; the relative Frobenius error is printed
+    beside it as information."""
     err = maxrel(got, want)
+    print("[parity] %-18s max-norm rel %.3e (tol %.1e)  Frobenius rel %.3e" % (name, err, tol, frobrel(got, want)), flush=True)
     assert err <= tol, "%s: max-norm relative error %.3e > %.1e" % (name, err, tol)
     return err
 

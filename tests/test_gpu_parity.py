@@ -261,37 +261,52 @@ def test_rmsnorm_and_residual(dtype, T, d):
 
 
 def test_cfg4_stack_teacher_forced_layers():
-    """h <- h + MoC(RMSNorm(h)) at the 7B shape, first layers of the 32-layer stack.  Each layer is
-    checked against the oracle on sampled token rows, feeding the oracle the GPU's own layer
-    input (after layer 1 the bf16 residual stream differs from float64 by far more than the
-    spacing of gate values at the threshold, so end-to-end index parity is not defined)."""
+    """h <- h + MoC(RMSNorm(h)) at the 7B shape, all 32 layers with independent weights.  Each layer
+    is checked against the oracle on one token row out of every band of 256 (so every row tile of
+    the gate / up launch is sampled) plus the first and the last row, feeding the oracle the GPU's
+    own layer input: after layer 1 the bf16 residual stream differs from float64 by far more than
+    the spacing of gate values at the threshold, so end-to-end index parity is not defined.  The
+    drift of the final residual stream against a float64 stack run on the sampled rows is printed
+    as information."""
+    from paper_2511_09323_amd.configs import STACK_LAYERS
     c = CONFIGS["cfg4"]
     T, d, F, K = c.T, c.d, c.F, c.K
-    n_layers = 3
-    rows = np.sort(np.random.default_rng(4).choice(T, size=48, replace=False))
-    h = P.to_dev(inputs.normal((T, d), inputs.seed_for(4, 0, "x"), 1.0, "bf16"), "bf16")
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, T - 1], np.arange(0, T, 256) + rng.integers(0, 256, size=T // 256)]))
+    sel = torch.from_numpy(rows).cuda()
+    h0_np = inputs.normal((T, d), inputs.seed_for(4, 0, "x"), 1.0, "bf16")
+    h = P.to_dev(h0_np, "bf16")
+    h_ref = h0_np[rows].astype(np.float64)          # float64 stack on the sampled rows (tokens are independent)
     gain_np = np.ones(d, dtype=np.float32)
     gain = P.to_dev(gain_np, "bf16")
     ws = torch.empty(moc.workspace_bytes(T, d, F, K, torch.bfloat16, 0), dtype=torch.uint8, device="cuda")
-    for layer in range(n_layers):
+    in_window = 0
+    for layer in range(STACK_LAYERS):
         say("[case] cfg4 stack layer %d" % layer)
         L = inputs.make_layer(4, 1, d, F, "bf16", layer=layer)
         Wd_ = {k: P.to_dev(L[k], "bf16") for k in ("wg", "wu", "wd")}
-        h_in = P.to_np(h[torch.from_numpy(rows).cuda()])
+        h_in = P.to_np(h[sel])
         xn = moc.moc_rmsnorm(h, gain, RMSNORM_EPS)
         y, idx, _, _ = moc.moc_ffn_fwd(xn, Wd_["wg"], Wd_["wu"], Wd_["wd"], K, ws=ws)
         moc.moc_residual_add(h, y)
         torch.cuda.synchronize()
-        sel = torch.from_numpy(rows).cuda()
         P.assert_close("rmsnorm", P.to_np(xn[sel]), O.rmsnorm(h_in, gain_np, RMSNORM_EPS), 1e-2)
         Ls = {"x": xn[sel].float().cpu().numpy(), "wg": L["wg"], "wu": L["wu"], "wd": L["wd"]}
         idx_np = idx[sel].cpu().numpy()
         D, _, _, G64 = P.oracle_forward_for(Ls, idx_np)
         window = P.check_index_sets(idx_np, G64, K)
+        in_window += len(window)
         assert len(window) <= 2
         P.assert_close("y", P.to_np(y[sel]), D, P.TOL["bf16"])
         P.assert_close("h", P.to_np(h[sel]), O.residual_add(h_in, P.to_np(y[sel])), 1e-2)
+        # the float64 stack on its own trajectory (own selection), for the drift figure only
+        Wg, Wu, Wdn = P.paper_weights(L)
+        Dr = O.moc_forward(O.rmsnorm(h_ref, gain_np, RMSNORM_EPS), Wg, Wu, Wdn, K)[0]
+        h_ref = O.residual_add(h_ref, Dr)
         del Wd_, L
+    drift = np.abs(P.to_np(h[sel]).astype(np.float64) - h_ref).max() / np.abs(h_ref).max()
+    say("[info] cfg4: %d sampled rows x %d layers, %d rows inside the near-tie window; max-norm drift of h_%d against "
+        "the float64 stack: %.3e" % (len(rows), STACK_LAYERS, in_window, STACK_LAYERS, drift))
 
 
 # ------------------------------------------------------------------------- graph capture
