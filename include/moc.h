@@ -25,7 +25,7 @@
  *    time must not share a workspace.  The only state kept between calls is a per-device set-up
  *    done once, by moc_init() or by the first entry point called with that device current: the
  *    dynamic-LDS limit of every kernel (hipFuncSetAttribute) and the device address of the static
- *    scratch array.  It is guarded by a mutex and makes no stream operation, so a first call may be
+ *    scratch array of moc_ffn_decode_static.  It is guarded by a mutex and makes no stream operation, so a first call may be
  *    made from any thread and under stream capture; a caller that wants the set-up outside its
  *    capture or timing calls moc_init() beforehand.
  *  - Calls validate their arguments on the host, enqueue kernels on `hip_stream` (a hipStream_t,
@@ -107,6 +107,19 @@ moc_status moc_ffn_bwd(const moc_shape* shape, const void* x, const void* wg, co
 moc_status moc_ffn_decode(const moc_shape* shape, const void* x, const void* wg, const void* wu,
                           const void* wd, void* y, int32_t* idx_or_null,
                           void* ws, size_t ws_bytes, void* hip_stream);
+
+/* moc_ffn_decode for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * kernels as moc_ffn_decode, but the scratch is a static device array inside the library
+ * (moc_static_scratch_bytes() = 16 MiB per GPU, held until the process ends); the call allocates
+ * nothing.  Shapes whose moc_workspace_bytes(shape, MOC_OP_DECODE) exceeds that size are refused
+ * with MOC_ERR_UNSUPPORTED before anything is launched (the 7B shape with 16 tokens needs about
+ * 6 MiB).  All calls on one GPU share the array: the kernels overwrite what they read, nothing has
+ * to be cleared between calls, but two calls that overlap in time on one GPU (different streams)
+ * race; order them on one stream or with events. */
+moc_status moc_ffn_decode_static(const moc_shape* shape, const void* x, const void* wg, const void* wu,
+                                 const void* wd, void* y, int32_t* idx_or_null, void* hip_stream);
+size_t moc_static_scratch_bytes(void);
 
 /* Dense SwiGLU FFN, Eqs. (FFN-1), (FFN-2): the K = F reference.  shape->K is ignored.
  * g_save, u_save are [T,F] in dtype (the dense stored set G and U). */

@@ -17,7 +17,7 @@ MOC_F32, MOC_BF16 = 0, 1
 OP_FWD, OP_BWD, OP_DECODE, OP_SWIGLU_FWD, OP_SWIGLU_BWD = range(5)
 
 EXPORTS = (
-    "moc_workspace_bytes", "moc_init", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_swiglu_fwd",
+    "moc_workspace_bytes", "moc_init", "moc_ffn_fwd", "moc_ffn_bwd", "moc_ffn_decode", "moc_ffn_decode_static", "moc_static_scratch_bytes", "moc_swiglu_fwd",
     "moc_swiglu_bwd", "moc_topk_rows", "moc_ffn_fwd_experts", "moc_ffn_bwd_experts", "moc_ffn_fwd_keyed", "moc_ffn_decode_keyed", "moc_topk_rows_keyed", "moc_ffn_fwd_grouped", "moc_ffn_decode_grouped", "moc_topk_grouped_rows", "moc_rmsnorm", "moc_residual_add", "moc_timing_enable",
     "moc_timing_collect", "moc_timing_get", "moc_timing_reset", "moc_status_string",
     "moc_last_error", "moc_version",
@@ -58,6 +58,10 @@ def load_library():
     lib.moc_ffn_bwd.argtypes = [shp] + [vp] * 13 + [sz, vp]
     lib.moc_ffn_decode.restype = ctypes.c_int
     lib.moc_ffn_decode.argtypes = [shp] + [vp] * 7 + [sz, vp]
+    lib.moc_ffn_decode_static.restype = ctypes.c_int
+    lib.moc_ffn_decode_static.argtypes = [shp] + [vp] * 6 + [vp]
+    lib.moc_static_scratch_bytes.restype = sz
+    lib.moc_static_scratch_bytes.argtypes = []
     lib.moc_swiglu_fwd.restype = ctypes.c_int
     lib.moc_swiglu_fwd.argtypes = [shp] + [vp] * 8 + [sz, vp]
     lib.moc_swiglu_bwd.restype = ctypes.c_int
@@ -227,6 +231,30 @@ def moc_ffn_decode(x, wg, wu, wd, K, ws=None, want_idx=True, out=None):
                               _ptr(idx, torch.int32, (B, K), "idx") if idx is not None else None,
                               _ptr(ws, name="ws"), ws_bytes, _stream()))
     return y, idx
+
+
+def moc_ffn_decode_static(x, wg, wu, wd, K, want_idx=True, out=None):
+    """moc_ffn_decode on the library's static scratch array: no workspace argument, no allocation
+    inside the call when `out` is given.  Returns (y, idx or None)."""
+    lib = load_library()
+    B, d = x.shape
+    F = wg.shape[0]
+    dt = x.dtype
+    code = _dtype_code(x)
+    if out is None:
+        y = torch.empty((B, d), dtype=dt, device=x.device)
+        idx = torch.empty((B, K), dtype=torch.int32, device=x.device) if want_idx else None
+    else:
+        y, idx = out
+    shp = _shape(B, d, F, K, code)
+    _check(lib.moc_ffn_decode_static(ctypes.byref(shp), _ptr(x, dt, (B, d), "x"), _ptr(wg, dt, (F, d), "wg"),
+                                     _ptr(wu, dt, (F, d), "wu"), _ptr(wd, dt, (F, d), "wd"), _ptr(y, dt, (B, d), "y"),
+                                     _ptr(idx, torch.int32, (B, K), "idx") if idx is not None else None, _stream()))
+    return y, idx
+
+
+def static_scratch_bytes():
+    return int(load_library().moc_static_scratch_bytes())
 
 
 def moc_swiglu_fwd(x, wg, wu, wd, ws=None, out=None):

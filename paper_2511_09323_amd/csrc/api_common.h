@@ -83,8 +83,10 @@ struct Options {          // environment, read once when the library is loaded
 };
 const Options& options();
 
-// Per-device set-up (kernel attributes); see moc_api.hip.
-moc_status ensure_init();
+// Per-device set-up (kernel attributes, address of the static scratch); see moc_api.hip.
+// scratch_out, if given, receives the current device's address of the static scratch array.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+moc_status ensure_init(void** scratch_out = nullptr);
 
 #define MOC_SETUP()                                  \
     do {                                             \

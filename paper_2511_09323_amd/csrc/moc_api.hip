@@ -13,6 +13,12 @@
 
 using namespace moc;
 
+// Scratch of moc_ffn_decode_static, the entry point for callers that cannot hand over a workspace.
+// Every GPU the library runs on holds its own copy until the process ends.  In host code the name
+// below is only a handle for hipGetSymbolAddress: ensure_init() asks for the device address once
+// per device, and everything else (kernel arguments) uses that address.
+static __device__ __align__(256) unsigned char scratch[mocapi::kStaticScratchBytes];
+
 namespace mocapi {
 
 thread_local char g_err[512] = "";
@@ -64,15 +70,17 @@ const Options& options() { return g_options; }
 
 // ------------------------------------------------------------------- per-device set-up
 // Done once per device, by the first entry point called with that device current (or by moc_init):
-// the dynamic-LDS limit of every kernel that registered one.  Nothing else is kept between calls.
+// the dynamic-LDS limit of every kernel that registered one, and the address of this device's copy
+// of the static scratch array.  Nothing else is kept between calls.
 constexpr int kMaxDevices = 64;
 struct DeviceState {
     std::atomic<int> ready{0};
+    void* scratch_ptr = nullptr;      // device address of this device's copy of `scratch`
 };
 DeviceState g_dev[kMaxDevices];
 std::mutex g_init_mu;
 
-moc_status ensure_init() {
+moc_status ensure_init(void** scratch_out) {
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return fail(MOC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
@@ -82,9 +90,14 @@ moc_status ensure_init() {
         if (!D.ready.load(std::memory_order_relaxed)) {
             for (const KernelAttr& a : kernel_attr_list())
                 HIP_TRY(hipFuncSetAttribute(a.fn, hipFuncAttributeMaxDynamicSharedMemorySize, a.lds_bytes));
+            void* p = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) return fail(MOC_ERR_HIP, "hipGetSymbolAddress gave no address for the static scratch");
+            D.scratch_ptr = p;
             D.ready.store(1, std::memory_order_release);
         }
     }
+    if (scratch_out) *scratch_out = D.scratch_ptr;
     return MOC_OK;
 }
 
@@ -138,6 +151,8 @@ size_t moc_workspace_bytes(const moc_shape* shape, int op) {
 }
 
 moc_status moc_init(void) { return ensure_init(); }
+
+size_t moc_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 moc_status moc_rmsnorm(int32_t T, int32_t d, int32_t dtype, const void* h, const void* gain, float eps, void* out,
                        void* hip_stream) {

@@ -204,6 +204,27 @@ moc_status moc_ffn_decode(const moc_shape* shape, const void* x, const void* wg,
                               idx_or_null, ws, st);
 }
 
+moc_status moc_ffn_decode_static(const moc_shape* shape, const void* x, const void* wg, const void* wu, const void* wd,
+                                 void* y, int32_t* idx_or_null, void* hip_stream) {
+    moc_status s = check_shape(shape, true);
+    if (s != MOC_OK) return s;
+    CHECK_PTR(x); CHECK_PTR(wg); CHECK_PTR(wu); CHECK_PTR(wd); CHECK_PTR(y);
+    if (idx_or_null && !aligned16(idx_or_null)) return fail(MOC_ERR_BAD_ARG, "idx is not 16-byte aligned");
+    const size_t need = moc_workspace_bytes(shape, MOC_OP_DECODE);
+    if (need > kStaticScratchBytes)
+        return fail(MOC_ERR_UNSUPPORTED, "decode scratch for this shape is %zu bytes, the static buffer holds %zu", need,
+                    kStaticScratchBytes);
+    void* ws = nullptr;                     // this device's copy of the static scratch array
+    if ((s = ensure_init(&ws)) != MOC_OK) return s;
+    Dims D(*shape);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (shape->dtype == MOC_BF16)
+        return decode_impl<bf16_t>(D, (const bf16_t*)x, (const bf16_t*)wg, (const bf16_t*)wu, (const bf16_t*)wd,
+                                   (bf16_t*)y, idx_or_null, ws, st);
+    return decode_impl<float>(D, (const float*)x, (const float*)wg, (const float*)wu, (const float*)wd, (float*)y,
+                              idx_or_null, ws, st);
+}
+
 moc_status moc_ffn_decode_keyed(const moc_shape* shape, int32_t key_mode, const void* x, const void* wg, const void* wu,
                                 const void* wd, void* y, int32_t* idx_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
     moc_status s = check_shape(shape, true);
