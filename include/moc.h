@@ -38,7 +38,9 @@
  *    MOC_FORCE_GENERIC=1 sends every GEMM to the generic fp32-FMA kernel and decode to
  *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 forces an MFMA tile shape;
  *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n switch off, or set the workgroup count of, the
- *    single-launch grouped decode kernel.  All are read once, when the library is loaded.
+ *    single-launch grouped decode kernel; MOC_DECODE_PERSISTENT=1 runs row-wide decode (moc_ffn_decode,
+ *    moc_ffn_decode_static) as one persistent launch instead of four launches (slower on the
+ *    measured shapes, kept for study).  All are read once, when the library is loaded.
  */
 #ifndef MOC_H
 #define MOC_H

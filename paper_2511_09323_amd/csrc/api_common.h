@@ -79,6 +79,7 @@ struct Options {          // environment, read once when the library is loaded
     int tile;             // MOC_GEMM_TILE=256|192|128 forces a tile shape, 0 = choose by problem size
     int decode_fused;     // MOC_DECODE_FUSED=0: grouped decode of one token as separate launches
     int decode_fused_p;   // MOC_DECODE_FUSED_P=n: workgroups of the single-launch grouped decode kernel, 0 = choose
+    int decode_persistent;  // MOC_DECODE_PERSISTENT=1: row-wide decode as one persistent launch (measured slower than the separate launches)
     Options();
 };
 const Options& options();
@@ -87,6 +88,7 @@ const Options& options();
 // scratch_out, if given, receives the current device's address of the static scratch array.
 constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 moc_status ensure_init(void** scratch_out = nullptr);
+int device_cu_count();          // compute units of the current device (after ensure_init)
 
 #define MOC_SETUP()                                  \
     do {                                             \
@@ -163,9 +165,17 @@ inline int decode_splits(int B, int K) {
 
 constexpr int kDecodeFusedMaxP = 512;
 
+constexpr size_t kDecodeSyncBytes = 32 * 1024;          // >= sizeof(moc::DecodeSync), checked where that type is known
+constexpr size_t kDecodePartBudget = (size_t)4 << 20;   // partial outputs of the persistent kernel's down projection
+
 struct DecodeWs {
     float *g, *gkeys, *gsel, *z, *part;
     int32_t* idx;
+    // persistent single-launch kernel: tagged gate values [T, ldF], tagged token mask and z' of every
+    // channel [F, 1 + token slots], partial outputs of its down projection, its flag words
+    uint64_t *g2, *zt;
+    float* part2;
+    void* sync;
     size_t bytes;
     DecodeWs(void* ws, const Dims& D) {
         Carver c(ws);
@@ -177,6 +187,11 @@ struct DecodeWs {
         // partial outputs: one per channel share, or one per workgroup of the single-launch grouped kernel
         const int shares = std::max(decode_splits(D.T, D.K), D.T == 1 ? kDecodeFusedMaxP : 0);
         part = c.take<float>((size_t)shares * D.T * D.d);
+        const int slots = D.T == 1 ? 1 : (D.T <= 4 ? 4 : 16);
+        g2 = c.take<uint64_t>((size_t)D.T * D.ldF);
+        zt = c.take<uint64_t>((size_t)D.F * (1 + slots));
+        part2 = c.take<float>(kDecodePartBudget / sizeof(float));
+        sync = c.take<unsigned char>(kDecodeSyncBytes);
         bytes = c.off;
     }
 };

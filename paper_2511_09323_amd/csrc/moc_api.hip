@@ -64,7 +64,8 @@ static int env_int(const char* name, int dflt) {
 }
 Options::Options()
     : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)),
-      decode_fused(env_int("MOC_DECODE_FUSED", 1)), decode_fused_p(env_int("MOC_DECODE_FUSED_P", 0)) {}
+      decode_fused(env_int("MOC_DECODE_FUSED", 1)), decode_fused_p(env_int("MOC_DECODE_FUSED_P", 0)),
+      decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
 static const Options g_options;
 const Options& options() { return g_options; }
 
@@ -76,6 +77,7 @@ constexpr int kMaxDevices = 64;
 struct DeviceState {
     std::atomic<int> ready{0};
     void* scratch_ptr = nullptr;      // device address of this device's copy of `scratch`
+    int num_cu = 0;
 };
 DeviceState g_dev[kMaxDevices];
 std::mutex g_init_mu;
@@ -94,11 +96,18 @@ moc_status ensure_init(void** scratch_out) {
             HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
             if (!p) return fail(MOC_ERR_HIP, "hipGetSymbolAddress gave no address for the static scratch");
             D.scratch_ptr = p;
+            HIP_TRY(hipDeviceGetAttribute(&D.num_cu, hipDeviceAttributeMultiprocessorCount, dev));
             D.ready.store(1, std::memory_order_release);
         }
     }
     if (scratch_out) *scratch_out = D.scratch_ptr;
     return MOC_OK;
+}
+
+int device_cu_count() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    return g_dev[dev].num_cu;
 }
 
 moc_status check_shape(const moc_shape* s, bool decode) {

@@ -2,7 +2,11 @@
 // C entry points.
 #include "api_common.h"
 #include "api_launch.h"
+#include <atomic>
+#include <random>
+
 #include "decode_kernels.h"
+#include "decode_persist.h"
 
 using namespace moc;
 using namespace mocapi;
@@ -89,6 +93,142 @@ moc_status launch_decode_fused(const Dims& D, const E* x, const E* wg, const E* 
     return launch_decode_fused_t<E, 1, 2>(D, x, wg, wu, wd, idx, part, P, st);
 }
 
+// ------------------------------------------------------- row-wide decode in one persistent launch
+static_assert(sizeof(DecodeSync) <= kDecodeSyncBytes, "workspace reserve for the decode flags");
+
+// Host call counter that makes the flag epochs of different calls differ (decode_persist.h); seeded
+// randomly so that flags left in reused memory by another process cannot match either.
+std::atomic<uint32_t> g_decode_salt{std::random_device{}()};
+
+constexpr int kPersistentDynLds = 158 * 1024;      // the persistent kernels also hold about 1.2 KB of static LDS
+
+struct DecodePlan {
+    bool ok = false;
+    int variant = 0;              // 0: row per wavefront, one token; 1: row per wavefront, up to 4; 2: MFMA gate, up to 16
+    int nt = 0, nch = 0, bt = 0;
+    int nwg = 0, P = 1, C = 1, rmax = 1;
+    int off_own = 0, off_over = 0;
+    size_t lds = 0;
+};
+
+// The single-launch kernel serves the row-wide Top-K on the raw gate when the shape fits its
+// assumptions (whole weight rows in registers, the gate row of a token in one workgroup's registers,
+// 16-byte column segments); everything else stays on the separate launches.
+template <class E>
+DecodePlan plan_persistent(const Dims& D, int num_cu) {
+    DecodePlan pl;
+    constexpr int CN = Chunk<E>::N;
+    const int B = D.T, d = D.d, F = D.F;
+    const bool bf16 = std::is_same<E, bf16_t>::value;
+    if (num_cu < kDecMaxB || options().force_generic || !options().decode_persistent) return pl;   // workgroup b selects for token b
+    if (d % CN != 0 || d > 64 * CN * 8) return pl;
+    if (B <= 4) {
+        pl.variant = B == 1 ? 0 : 1;
+        pl.bt = B == 1 ? 1 : 4;
+        pl.nt = 1024;
+    } else {
+        if (!bf16 || d % 1024 != 0) return pl;
+        pl.variant = 2;
+        pl.bt = 16;
+        pl.nt = 768;
+    }
+    const int nwv = pl.nt / 64;
+    const int nch = (F + pl.nt * 4 - 1) / (pl.nt * 4);
+    pl.nch = nch <= 3 ? 3 : (nch <= 4 ? 4 : 8);
+    if (nch > 8) return pl;
+    pl.nwg = std::min(num_cu, kDecMaxWG);
+    // x, own gate values, phase-overlaid area
+    const size_t xbytes = pl.variant == 2 ? (size_t)16 * (d * 2 + 16) : (size_t)pl.bt * d * sizeof(E);
+    size_t own;
+    if (pl.variant == 2) {
+        const int nblk = (F + 47) / 48;
+        pl.rmax = (nblk + pl.nwg - 1) / pl.nwg;
+        own = (size_t)pl.rmax * 48 * 17 * sizeof(float);
+    } else {
+        pl.rmax = (F + pl.nwg * nwv - 1) / (pl.nwg * nwv);
+        own = (size_t)nwv * pl.rmax * pl.bt * sizeof(float);
+    }
+    pl.off_own = (int)round_up_sz(xbytes, 16);
+    pl.off_over = (int)round_up_sz(pl.off_own + own, 16);
+    const size_t over = std::max(kDecSelLds, pl.variant == 2 ? (size_t)12 * 256 * sizeof(float) : (size_t)0);
+    // down projection: C column slices of LPR 16-byte chunks each, P channel ranges
+    const int total = (int)((size_t)d * sizeof(E) / 16);
+    const int tb = pl.bt > 8 ? 8 : pl.bt;
+    int best_lpr = 0;
+    size_t best_vol = 0;
+    bool best_good = false;
+    for (int lpr = 64; lpr >= 1; lpr >>= 1) {
+        if (total % lpr != 0) continue;
+        const int C = total / lpr;
+        if (C > pl.nwg) continue;
+        // the last B workgroups write the index lists: they get no share of the down projection if possible
+        const int P = std::max(1, std::min(std::max(pl.nwg - B, C) / C, F));
+        const int seg = d / C;
+        const size_t vol = (size_t)P * B * d * sizeof(float), last = (size_t)P * B * seg * sizeof(float);
+        const size_t dl = round_up_sz(((size_t)(F + P - 1) / P + 1) * 8, 16) + (size_t)nwv * tb * seg * sizeof(float);
+        if (dl > (size_t)kPersistentDynLds || vol > kDecodePartBudget) continue;
+        const bool good = last <= 96 * 1024;
+        if (best_lpr == 0 || (good && !best_good) || (good == best_good && !good && vol < best_vol)) {
+            if (best_lpr != 0 && best_good) continue;        // keep the first (widest) good split
+            best_lpr = lpr; best_vol = vol; best_good = good;
+        }
+    }
+    if (best_lpr == 0) return pl;
+    pl.C = total / best_lpr;
+    pl.P = std::max(1, std::min(std::max(pl.nwg - B, pl.C) / pl.C, F));
+    const size_t dl = round_up_sz(((size_t)(F + pl.P - 1) / pl.P + 1) * 8, 16) + (size_t)nwv * tb * (d / pl.C) * sizeof(float);
+    // more than half of a compute unit's LDS, so that the dispatcher places one workgroup per unit
+    pl.lds = std::max(std::max((size_t)pl.off_over + over, dl), (size_t)84 * 1024);
+    if (pl.lds > (size_t)kPersistentDynLds) return pl;
+    pl.ok = true;
+    return pl;
+}
+
+template <class E, int BT, int NCH>
+moc_status launch_persistent_rows(const DecodePlan& pl, const DecArgs<E>& a, hipStream_t st) {
+    auto kern = decode_persistent_kernel<E, BT, 1024, NCH>;
+    LdsAttr<decode_persistent_kernel<E, BT, 1024, NCH>, kPersistentDynLds>::use();
+    Span span("decode_persistent", st);
+    hipLaunchKernelGGL(kern, dim3(pl.nwg), dim3(1024), pl.lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <int NCH>
+moc_status launch_persistent_mfma(const DecodePlan& pl, const DecArgs<bf16_t>& a, hipStream_t st) {
+    auto kern = decode_persistent_mfma_kernel<NCH>;
+    LdsAttr<decode_persistent_mfma_kernel<NCH>, kPersistentDynLds>::use();
+    Span span("decode_persistent", st);
+    hipLaunchKernelGGL(kern, dim3(pl.nwg), dim3(768), pl.lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+
+template <class E>
+moc_status decode_persistent(const DecodePlan& pl, const Dims& D, const DecodeWs& W, const E* x, const E* wg, const E* wu,
+                             const E* wd, E* y, int32_t* idx, hipStream_t st) {
+    DecArgs<E> a;
+    a.x = x; a.wg = wg; a.wu = wu; a.wd = wd; a.y = y; a.idx = idx;
+    a.B = D.T; a.d = D.d; a.F = D.F; a.K = D.K; a.ldF = D.ldF;
+    a.g2 = W.g2; a.zt = W.zt; a.part = W.part2;
+    a.sync = static_cast<DecodeSync*>(W.sync);
+    a.salt = g_decode_salt.fetch_add(1, std::memory_order_relaxed);
+    a.P = pl.P; a.C = pl.C; a.rmax = pl.rmax; a.off_own = pl.off_own; a.off_over = pl.off_over;
+    if (pl.variant == 0)
+        return pl.nch == 3   ? launch_persistent_rows<E, 1, 3>(pl, a, st)
+               : pl.nch == 4 ? launch_persistent_rows<E, 1, 4>(pl, a, st)
+                             : launch_persistent_rows<E, 1, 8>(pl, a, st);
+    if (pl.variant == 1)
+        return pl.nch == 3   ? launch_persistent_rows<E, 4, 3>(pl, a, st)
+               : pl.nch == 4 ? launch_persistent_rows<E, 4, 4>(pl, a, st)
+                             : launch_persistent_rows<E, 4, 8>(pl, a, st);
+    if constexpr (std::is_same<E, bf16_t>::value)
+        return pl.nch == 3   ? launch_persistent_mfma<3>(pl, a, st)
+               : pl.nch == 4 ? launch_persistent_mfma<4>(pl, a, st)
+                             : launch_persistent_mfma<8>(pl, a, st);
+    return fail(MOC_ERR_UNSUPPORTED, "decode: no single-launch kernel for this shape");
+}
+
 // ga:gb = 0:0 is the row-wide Top-K; otherwise the grouped selection of MoC_{a:b}, which is decided
 // inside the gate kernel (a group's channels meet in one workgroup) and needs no selection launch.
 template <class E>
@@ -98,6 +238,11 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     const int B = D.T;
     int32_t* idx = idx_out ? idx_out : W.idx;
     moc_status s;
+    if (gb == 0 && key_mode == 0) {
+        // row-wide Top-K on the raw gate: gate, selection, up and down projection in one launch
+        const DecodePlan pl = plan_persistent<E>(D, device_cu_count());
+        if (pl.ok) return decode_persistent<E>(pl, D, W, x, wg, wu, wd, y, idx, st);
+    }
     // MOC_DECODE_FUSED=0 keeps grouped decode on the separate gate+select and gather launches;
     // MOC_DECODE_FUSED_P=n sets the workgroup count of the single-launch kernel.
     if (gb == 8 && (ga == 1 || ga == 2) && B == 1 && D.d <= 8 * 64 * Chunk<E>::N && options().decode_fused &&

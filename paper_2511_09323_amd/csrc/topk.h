@@ -288,19 +288,31 @@ __global__ __launch_bounds__(NT) void topk_rows_lds_kernel(TopkArgs<E> a) {
 // in LDS at their output slot, so that the compact outputs are written slot by slot (coalesced,
 // SiLU evaluated K times instead of under divergence for every channel) and the dense Z' row is
 // assembled in LDS and streamed out with 16-byte stores.  Dynamic LDS: topk_reg_dyn_lds().
+//
+// The work of one row is a device function: `row` selects the row, topk_dyn is the caller's LDS area
+// of topk_reg_dyn_lds() bytes, `write_out` = false skips every global store (the caller only wants
+// the threshold), and the return value describes the selected set without the index list: a channel j with key k belongs
+// to it iff k > tau, or k == tau and j <= cut (cut = INT_MAX when every key equal to tau is in).
+struct TopkThreshold {
+    uint32_t tau;
+    int cut;
+};
+
+__device__ __forceinline__ bool topk_member(uint32_t key, int j, TopkThreshold t) {
+    return key > t.tau || (key == t.tau && j <= t.cut);
+}
+
 template <class E, int NT, int NCH, bool FUSED>
-__global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
+__device__ __forceinline__ TopkThreshold topk_row_body(const TopkArgs<E>& a, int64_t row, unsigned char* topk_dyn, bool write_out) {
     constexpr int NW = NT / 64;
     constexpr int CHUNK = NT * 4;
-    extern __shared__ __align__(16) unsigned char topk_dyn[];       // histograms, later slot lists + dense row
-    uint32_t (*hist)[kTopkBins] = reinterpret_cast<uint32_t (*)[kTopkBins]>(topk_dyn);
+    uint32_t (*hist)[kTopkBins] = reinterpret_cast<uint32_t (*)[kTopkBins]>(topk_dyn);     // histograms, later slot lists + dense row
     __shared__ int tab_gt[NCH * NW], tab_eq[NCH * NW];
     __shared__ int red[NW];
     __shared__ uint32_t sh_prefix;
-    __shared__ int sh_need, sh_cnt;
+    __shared__ int sh_need, sh_cnt, sh_cut;
     const int F = a.F, K = a.K;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row = blockIdx.x;
     const float* grow = a.g + row * a.ldg;
 
     // ---- all loads of the row up front
@@ -375,9 +387,11 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             // Suffix scan over all kTopkBins counters by the whole workgroup (a 10-bit pass leaves the
             // upper half at zero): thread t owns the BPT bins below kTopkBins - BPT t, so thread order
             // is descending bin order; the thread whose range crosses `need` publishes the result.
-            constexpr int BPT = kTopkBins / NT;
-            static_assert(BPT == 2 || BPT == 4 || BPT == 8, "bins per thread");
-            const int base = kTopkBins - BPT * (tid + 1);
+            // (a workgroup size that does not divide the bins, 768, leaves its last threads without bins)
+            constexpr int BPT = NT >= 1024 ? 2 : (NT >= 512 ? 4 : 8);
+            static_assert(BPT * NT >= kTopkBins, "bins per thread");
+            const bool owner = BPT * (tid + 1) <= kTopkBins;
+            const int base = owner ? kTopkBins - BPT * (tid + 1) : 0;
             uint32_t hv[BPT];
             if (BPT == 2) {
                 const u32x2_t t2 = *reinterpret_cast<const u32x2_t*>(cur + base);
@@ -388,6 +402,10 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                     const u32x4_t t4 = *reinterpret_cast<const u32x4_t*>(cur + base + q);
                     hv[q] = t4[0]; hv[q + 1] = t4[1]; hv[q + 2] = t4[2]; hv[q + 3] = t4[3];
                 }
+            }
+            if (!owner) {
+#pragma unroll
+                for (int q = 0; q < BPT; ++q) hv[q] = 0;
             }
             int local = 0;
 #pragma unroll
@@ -405,7 +423,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
             for (int w = 0; w < NW; ++w) before += (w < wave) ? red[w] : 0;
             inc += before;
             const int above = inc - local;
-            if (above < need && inc >= need) {               // the crossing bin is one of mine
+            if (owner && above < need && inc >= need) {      // the crossing bin is one of mine
                 int run = above, fb = -1, fneed = 0, fh = 0;
 #pragma unroll
                 for (int q = BPT - 1; q >= 0; --q) {         // descending bins
@@ -499,6 +517,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         constexpr int PER = 16 / (int)sizeof(E);
         for (int i = tid * PER; i < ldz; i += NT * PER) *reinterpret_cast<u32x4_t*>(zrow + i) = u32x4_t{0, 0, 0, 0};
     }
+    if (tid == 0) sh_cut = 0x7FFFFFFF;
     __syncthreads();
 
     // ---- rank: every selected channel drops (channel, gate value, up value) into LDS at its
@@ -539,6 +558,7 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
                     r[0] = (uint32_t)(j0 + e);
                     r[1] = k;
                     if (FUSED) r[2] = __float_as_uint(uu[e]);
+                    if (iseq && eq_before == need - 1) sh_cut = j0 + e;     // the last tie that is taken
                 }
                 gt_before += isgt ? 1 : 0;
                 eq_before += iseq ? 1 : 0;
@@ -546,6 +566,8 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         }
     }
     __syncthreads();
+    const TopkThreshold result{tau, sh_cut};
+    if (!write_out) return result;
     // ---- write the compact outputs slot by slot (coalesced) and scatter z' into the dense row
     for (int sl = tid; sl < K; sl += NT) {
         const int j = min((int)rec[3 * sl], F - 1);       // the clamp only matters for non-finite input
@@ -566,6 +588,13 @@ __global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
         for (int i = tid * PER; i < ldz; i += NT * PER)
             *reinterpret_cast<u32x4_t*>(zout + i) = *reinterpret_cast<const u32x4_t*>(zrow + i);
     }
+    return result;
+}
+
+template <class E, int NT, int NCH, bool FUSED>
+__global__ __launch_bounds__(NT) void topk_rows_kernel(TopkArgs<E> a) {
+    extern __shared__ __align__(16) unsigned char topk_dyn[];
+    topk_row_body<E, NT, NCH, FUSED>(a, blockIdx.x, topk_dyn, true);
 }
 
 // Dynamic LDS of topk_rows_kernel: two digit histograms, reused for the three slot lists and, in

@@ -353,6 +353,67 @@ def test_forward_backward_and_decode_replay_from_a_graph():
             assert torch.equal(g, w), "replay %d differs from the eager run" % rep
 
 
+@pytest.mark.parametrize("B", [1, 4, 16])
+def test_decode_workspace_reuse_and_ties(B):
+    run_decode_reuse_case(B, 1024, 2752, 344)
+
+
+def test_persistent_single_launch_decode():
+    """MOC_DECODE_PERSISTENT=1 (read once per process, hence the child process) runs row-wide decode as one
+    persistent launch: gate, exact selection, union gather of W_up and W_down with data-flow
+    synchronisation between the workgroups.  Same oracle checks as the default path, at the 7B shape for
+    1, 4 and 16 tokens (both kernel variants), on small and odd shapes, twice in a row on one workspace
+    (the tag of a call must not match what the previous call left), and bit-identical on repetition."""
+    import os
+    import subprocess
+    code = ("import torch\n"
+            "import tests.test_gpu_parity as t\n"
+            "from paper_2511_09323_amd.configs import CONFIGS\n"
+            "c = CONFIGS['cfg3']\n"
+            "for B in (1, 4, 16):\n"
+            "    t.run_decode_case('cfg3-persistent', 3, B, c.d, c.F, c.K, 'bf16', x_seed_offset=B)\n"
+            "for B, d, F, K, dt in ((3, 64, 100, 9, 'bf16'), (2, 36, 50, 50, 'f32'), (9, 1024, 333, 40, 'bf16'),\n"
+            "                       (16, 2048, 1000, 125, 'bf16'), (1, 512, 1376, 172, 'f32'), (4, 768, 2048, 256, 'bf16')):\n"
+            "    t.run_decode_case('small-persistent', 94, B, d, F, K, dt)\n"
+            "for B in (1, 4, 16):\n"
+            "    t.run_decode_reuse_case(B, 1024, 2752, 344)\n"
+            "print('ok')\n")
+    env = dict(os.environ, MOC_DECODE_PERSISTENT="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
+
+
+def run_decode_reuse_case(B, d, F, K):
+    """Three decode calls on ONE workspace with different inputs, then the first again: every result must
+    equal that of a fresh workspace bit for bit (nothing a call leaves in the workspace may leak into the
+    next), and tied gate values (a repeated weight row) must be cut at the lower channel."""
+    dt = torch.bfloat16
+    ws = torch.empty(moc.workspace_bytes(B, d, F, K, dt, 2), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xAB)                                 # not zero: the kernels must not rely on a cleared workspace
+    cases = []
+    for s in range(3):
+        L = inputs.make_layer(96 + s, B, d, F, "bf16")
+        if s == 1:
+            L["wg"][7] = L["wg"][3]                # channels 3 and 7 tie for every token
+            L["wg"][F - 1] = L["wg"][3]
+        cases.append({k: P.to_dev(v, "bf16") for k, v in L.items()})
+    fresh = []
+    for G in cases:
+        y, idx = moc.moc_ffn_decode(G["x"], G["wg"], G["wu"], G["wd"], K)
+        fresh.append((y.clone(), idx.clone()))
+    for rep in (0, 1, 2, 0, 0):
+        G = cases[rep]
+        y, idx = moc.moc_ffn_decode(G["x"], G["wg"], G["wu"], G["wd"], K, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, fresh[rep][1]) and torch.equal(y, fresh[rep][0]), "reuse %d" % rep
+    # the tied channels: never 7 without 3, never the last one without 7
+    idx1 = fresh[1][1].cpu().numpy()
+    for row in idx1:
+        s = set(row.tolist())
+        assert not (7 in s and 3 not in s) and not (F - 1 in s and 7 not in s)
+
+
 def test_generic_kernels_serve_bf16_when_forced():
     """MOC_FORCE_GENERIC=1 (read once per process, hence the child process) routes every bf16 GEMM to the
     fp32-FMA kernel and decode to its non-MFMA kernels; results must still match the oracle."""
