@@ -35,11 +35,37 @@ def parse():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-grouped", action="store_true", help="skip the MoC 2:8 (grouped Top-K) legs")
     ap.add_argument("--no-experts", action="store_true", help="skip the MoC-in-MoE-experts leg")
+    ap.add_argument("--no-small", action="store_true", help="skip the cfg0 (fp32 forward) and cfg1 (small fwd+bwd) legs")
+    ap.add_argument("--no-clocks", action="store_true",
+                    help="do not start rocm-smi after the run (a child process of a profiled run is refused on the GPU boxes)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="run only moc_residual_add on 2 x 512 MiB (known traffic: 1 GiB read, 512 MiB written per "
                          "launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
     return ap.parse_args()
+
+
+def source_hash():
+    from paper_2511_09323_amd.build import source_hash as h
+    return h()
+
+
+def committed_traffic(kernel_key, lib_version):
+    """HBM bytes per launch of `kernel_key` from the committed rocprofv3 counter summary, or None when that
+    summary was not taken on the sources this library was built from."""
+    tpath = os.path.join(ROOT, "profiles", "cfg2_traffic.json")
+    if not os.path.exists(tpath):
+        return None, "no committed counter summary"
+    tj = json.load(open(tpath))
+    here = source_hash()
+    if tj.get("_source_hash") != here:
+        return None, "committed counter summary is for other sources (%s, these are %s)" % (tj.get("_source_hash"), here)
+    if ("src:" + here) not in lib_version:
+        return None, "the library was not built from these sources (%s)" % lib_version
+    ent = tj.get(kernel_key)
+    if not ent:
+        return None, "kernel not in the committed counter summary"
+    return ent["hbm_read_bytes"] + ent["hbm_written_bytes"], "profiles/cfg2_traffic.json, same source hash %s" % here
 
 
 def gemm_flops(T, d, F, K):
@@ -135,8 +161,13 @@ def main():
     # algorithmic HBM bytes per launch of the two streaming kernels (bf16 activations):
     #   Top-K + SiLU.U: reads G fp32 and U, writes the dense Z' row and the stored set (idx, gvals, uvals);
     #   pointwise + expansion: reads the stored set and the dense dZ' row, writes Z', dG, dU rows.
+    # executed: what these kernels move in this design (dense U in, dense-masked rows out);
+    # algorithmic: what the method needs (gate row in + stored set out; stored set + dZ' at the selected
+    # channels in, z', dG, dU at the selected channels out)
     hbm_bytes = {"topk_select_act": T * (4 * F + 2 * F + 2 * ldF + K * 8),
                  "bwd_pointwise_expand": T * (K * 8 + 2 * ldF + 3 * 2 * ldF)}
+    hbm_algo = {"topk_select_act": T * (4 * F + K * (4 + 2)),
+                "bwd_pointwise_expand": T * (K * (4 + 2 * 2) + K * 2 + 3 * K * 2)}
     kernels = []
     for name, (ms, n) in sorted(timing.items(), key=lambda kv: -kv[1][0]):
         avg_ms = ms / max(n, 1)
@@ -147,25 +178,39 @@ def main():
             row["algorithmic_tflops"] = round(al / (avg_ms * 1e-3) / 1e12, 2)
             row["frac_executed"] = round(row["executed_tflops"] / PEAK_BF16_TFLOPS, 4)
         if name in hbm_bytes:
-            row["algorithmic_GBs"] = round(hbm_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
-            row["frac_hbm_peak"] = round(row["algorithmic_GBs"] / PEAK_HBM_GBS, 4)
+            row["executed_GBs"] = round(hbm_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
+            row["frac_hbm_peak_executed"] = round(row["executed_GBs"] / PEAK_HBM_GBS, 4)
+            row["algorithmic_GBs"] = round(hbm_algo[name] / (avg_ms * 1e-3) / 1e9, 1)
+            row["frac_hbm_peak_algorithmic"] = round(row["algorithmic_GBs"] / PEAK_HBM_GBS, 4)
         kernels.append(row)
-    # roofline entry: the gate GEMM, the one contraction whose algorithmic FLOPs (2 d F per token)
-    # equal the executed ones.  HBM traffic per launch comes from the committed rocprofv3 counter
-    # summary (profiles/), not from this run.
-    gate = next((r for r in kernels if r["kernel"] == "gemm_gate"), None)
+    # roofline: the top-level keys describe the dominant kernel of the step (largest share of the time);
+    # `entries` adds the gate GEMM (the one contraction whose algorithmic FLOPs, 2 d F per token, equal
+    # the executed ones) and, further down, the whole decode call.  `achieved` / `frac` are ALGORITHMIC
+    # FLOP/s (2 d K per token and product for the gathered contractions); the executed (dense-tile)
+    # rate stands beside them.  HBM traffic per launch comes from the committed rocprofv3 counter
+    # summary, and only when that summary was taken on the sources this library was built from.
+    traffic_keys = {"gemm_gate": "gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>",
+                    "gemm_dw3": "gemm_bf16_mfma_batch3<256,192,KM,KM,tail0,EpiStore<bf16>>"}
+
+    def roofline_entry(row):
+        name = row["kernel"]
+        ex, al = flops[name]
+        traffic, note = (None, "not measured for this kernel")
+        if args.workload == "cfg2" and name in traffic_keys:
+            traffic, note = committed_traffic(traffic_keys[name], moc.version())
+        return {"kernel": name, "bound": "mfma", "achieved": row["algorithmic_tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(row["algorithmic_tflops"] / PEAK_BF16_TFLOPS, 4),
+                "achieved_executed": row["executed_tflops"], "frac_executed": row["frac_executed"],
+                "traffic": traffic, "traffic_source": note, "avg_ms": row["avg_ms"],
+                "flops_per_launch": al, "executed_flops_per_launch": ex,
+                "timing": "HIP events around every launch, recorded by the library on the launch stream"}
+
+    gemm_rows = [r for r in kernels if r["kernel"] in flops]
     roofline = None
-    if gate:
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "cfg2_traffic.json")
-        if args.workload == "cfg2" and os.path.exists(tpath):
-            tj = json.load(open(tpath))
-            ent = tj.get("gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>")
-            if ent:
-                traffic = ent["hbm_read_bytes"] + ent["hbm_written_bytes"]
-        roofline = {"kernel": "gemm_gate", "bound": "mfma", "achieved": gate["executed_tflops"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(gate["executed_tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                    "avg_ms": gate["avg_ms"], "flops_per_launch": flops["gemm_gate"][1]}
+    if gemm_rows:
+        dominant = max(gemm_rows, key=lambda r: r["avg_ms"])
+        roofline = roofline_entry(dominant)
+        roofline["entries"] = [roofline_entry(r) for r in gemm_rows if r["kernel"] in ("gemm_gate", "gemm_gate_up") and r is not dominant]
     gemm_ms = sum(r["avg_ms"] for r in kernels if r["kernel"] in flops)
     gemm_ex = sum(flops[r["kernel"]][0] for r in kernels if r["kernel"] in flops)
     gemm_al = sum(flops[r["kernel"]][1] for r in kernels if r["kernel"] in flops)
@@ -197,10 +242,24 @@ def main():
                  "saved_activation_bytes": 2 * T * F * 2, "moc_saved_activation_bytes": T * K * (4 + 2 * 2)}
         del ws_df, ws_db, out_df
 
-    # decode leg: 7B shape, cold weights (rotating through independent weight sets)
+    # decode leg: 7B shape, cold weights (rotating through independent weight sets); the dense FFN through
+    # the same entry point (K = d_ff: every channel selected) is the in-library comparison
     decode = None
     if not args.no_decode:
         decode = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev)
+        decode["dense_K_equals_F"] = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, dense=True)["batches"]
+        if roofline is not None:
+            roofline["entries"] += [
+                {"kernel": "moc_ffn_decode, whole call, B=%d" % b["B"], "bound": "hbm", "achieved": b["effective_GBs"],
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": b["frac_hbm_peak"], "traffic": None,
+                 "bytes_per_call": int(b["algorithmic_MB"] * 1e6), "us_per_call": b["cold_us_median"],
+                 "timing": "HIP events around the whole call, cold weights"} for b in decode["batches"]]
+
+    # the two small configurations: cfg0 (fp32 forward) and cfg1 (bf16 forward + backward)
+    small = None
+    if not args.no_small:
+        small = {"cfg0": small_leg(torch, moc, inputs, CONFIGS["cfg0"], 0, dev, backward=False),
+                 "cfg1": small_leg(torch, moc, inputs, CONFIGS["cfg1"], 1, dev, backward=True)}
 
     # prefill-stack leg: 32 x [RMSNorm -> MoC FFN forward -> residual add] at the 7B shape
     stack = None
@@ -224,7 +283,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(L, K, args.cpu_sample_tokens)
 
-    line_clocks = gpu_clocks()
+    line_clocks = None if args.no_clocks else gpu_clocks()
     line = {
         "metric": "MoC FFN fwd+bwd tokens/s (1B shape) + decode effective HBM GB/s vs peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -233,7 +292,8 @@ def main():
         "config": {"workload": "%s: one MoC FFN layer fwd+bwd, T=%d d_model=%d d_ff=%d K=%d" % (args.workload, T, d, F, K),
                    "T": T, "d_model": d, "d_ff": F, "K": K},
         "roofline": roofline, "cpu_baseline": cpu, "all_gemms": all_gemms, "kernels": kernels, "dense_swiglu": dense,
-        "decode": decode, "prefill_stack": stack, "grouped_2of8": grouped, "moe_experts": experts, "clocks_after_run": line_clocks,
+        "decode": decode, "small_configs": small, "prefill_stack": stack, "grouped_2of8": grouped, "moe_experts": experts,
+        "clocks_after_run": line_clocks, "library": moc.version(), "source_hash": source_hash(),
     }
     print(json.dumps(line))
 
@@ -413,8 +473,43 @@ def grouped_train_leg(torch, moc, inputs, cfg, a, b, steps, warmup, dev):
             "group_select_frac_hbm_peak": round(sel_bytes / (sel * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if sel else None}
 
 
-def decode_leg(torch, moc, inputs, cfg, batches, dev, group=None):
+def small_leg(torch, moc, inputs, cfg, cfg_index, dev, backward):
+    """cfg0 / cfg1: far too small for any roofline (a few GFLOP); time and tokens/s only."""
+    T, d, F, K = cfg.T, cfg.d, cfg.F, cfg.K
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    L = inputs.make_layer(cfg_index, T, d, F, cfg.dtype, with_dy=backward)
+    G = {k: torch.from_numpy(v).to(dev).to(dt).contiguous() for k, v in L.items()}
+    ws_f = torch.empty(moc.workspace_bytes(T, d, F, K, dt, 0), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(moc.workspace_bytes(T, d, F, K, dt, 1), dtype=torch.uint8, device=dev) if backward else None
+    out_f = (torch.empty((T, d), dtype=dt, device=dev), torch.empty((T, K), dtype=torch.int32, device=dev),
+             torch.empty((T, K), dtype=dt, device=dev), torch.empty((T, K), dtype=dt, device=dev))
+    out_b = (torch.empty((T, d), dtype=dt, device=dev),) + tuple(torch.empty((F, d), dtype=dt, device=dev) for _ in range(3))
+
+    def step():
+        y, idx, gv, uv = moc.moc_ffn_fwd(G["x"], G["wg"], G["wu"], G["wd"], K, ws=ws_f, out=out_f)
+        if backward:
+            moc.moc_ffn_bwd(G["x"], G["wg"], G["wu"], G["wd"], idx, gv, uv, G["dy"], ws=ws_b, out=out_b)
+
+    for _ in range(20):
+        step()
+    torch.cuda.synchronize()
+    n = 200
+    t0 = time.perf_counter()
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    executed = (18.0 if backward else 6.0) * T * d * F
+    return {"workload": "%s: %s, T=%d d_model=%d d_ff=%d K=%d %s" % (cfg.name, "forward + backward" if backward else "forward",
+                                                                    T, d, F, K, cfg.dtype),
+            "ms_per_step": round(ms, 4), "tokens_per_s": round(T / (ms * 1e-3), 1),
+            "executed_tflops": round(executed / (ms * 1e-3) / 1e12, 2)}
+
+
+def decode_leg(torch, moc, inputs, cfg, batches, dev, group=None, dense=False):
     d, F, K = cfg.d, cfg.F, cfg.K
+    if dense:
+        K = F
     if group is not None:
         K = F // group[1] * group[0]
     bf = torch.bfloat16
@@ -481,9 +576,14 @@ def decode_leg(torch, moc, inputs, cfg, batches, dev, group=None):
         out.append({"B": B, "cold_us_median": round(med, 2), "cold_us_min": round(us[0], 2), "warm_us": round(warm_us, 2),
                     "union_channels": round(union, 1), "algorithmic_MB": round(algo_bytes / 1e6, 2),
                     "effective_GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
-                    "kernels_us": kern_us})
+                    "kernels_us_event_bracketed": kern_us})
     sel = "row-wide Top-K" if group is None else "grouped Top-K %d:%d" % group
+    if dense:
+        sel = "dense FFN through moc_ffn_decode (K = d_ff)"
     return {"workload": "cfg3: d_model=%d d_ff=%d K=%d bf16, %s, cold weights (8 rotating sets)" % (d, F, K, sel),
+            "timing": "cold_us_*: HIP events around the whole call; kernels_us_event_bracketed: a separate pass with events around "
+                      "every launch, which adds 2-3 us per launch, so their sum exceeds the call time (rocprofv3 durations are "
+                      "in profiles/cfg3_decode_kernel_stats.md)",
             "batches": out}
 
 

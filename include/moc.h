@@ -34,13 +34,23 @@
  *  - Errors: a negative moc_status is returned and moc_last_error() describes it (thread-local
  *    text).  Argument errors are found before anything is launched and leave outputs untouched.
  *  - Limits: 1 <= K <= F <= 32768, T >= 1 (T <= 16 for decode), d >= 1; MOC_BF16 needs d % 8 == 0.
+ *    Tighter limits, all refused with MOC_ERR_UNSUPPORTED before anything is launched:
+ *    moc_ffn_bwd_experts stages three rows of F_pad elements in LDS, so it needs
+ *    3 * F_pad * sizeof(element) <= 160 KiB - 64 (F <= ~27k for bf16, ~13.6k for fp32; plain
+ *    moc_ffn_bwd has no such limit).  The decode entry points stage the tokens' inputs in LDS:
+ *    Bt * d * sizeof(element) <= 160 KiB - 64 with Bt = 1, 4 or 16 for T = 1, 2..4, 5..16
+ *    (fp32 with T > 4: d <= 2559; bf16 with T > 4 and d not a multiple of 1024: d <= 5119), and
+ *    d * sizeof(element) <= 64 KiB for the gather stage.
  *  - Environment variables for testing and tuning (none is needed in normal use):
  *    MOC_FORCE_GENERIC=1 sends every GEMM to the generic fp32-FMA kernel and decode to
  *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 forces an MFMA tile shape;
  *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n switch off, or set the workgroup count of, the
  *    single-launch grouped decode kernel; MOC_DECODE_PERSISTENT=1 runs row-wide decode (moc_ffn_decode,
  *    moc_ffn_decode_static) as one persistent launch instead of four launches (slower on the
- *    measured shapes, kept for study).  All are read once, when the library is loaded.
+ *    measured shapes, kept for study); MOC_GEMM_PERSISTENT=0 launches one workgroup per GEMM tile
+ *    instead of one per compute unit looping over tiles; MOC_BWD_EPILOGUE=1 applies the backward's
+ *    pointwise step in the dZ' product's epilogue instead of a kernel of its own (slower as measured).
+ *    All are read once, when the library is loaded.
  */
 #ifndef MOC_H
 #define MOC_H
@@ -221,7 +231,8 @@ void moc_timing_reset(void);
 
 const char* moc_status_string(int status);
 const char* moc_last_error(void);
-/* Library version string, e.g. "moc-ffn 0.1 gfx950". */
+/* Library version string, e.g. "moc-ffn 0.2 gfx950 src:0123456789abcdef": the last field is a hash of
+ * the sources the library was built from. */
 const char* moc_version(void);
 
 #ifdef __cplusplus

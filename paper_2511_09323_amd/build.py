@@ -3,6 +3,7 @@
 The entry points are spread over four translation units that are compiled side by side and
 linked into one shared library.
 """
+import hashlib
 import os
 import subprocess
 import sys
@@ -18,6 +19,20 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ] + os.environ.get("MOC_EXTRA_HIPCC_FLAGS", "").split()
+
+
+def source_hash():
+    """Content hash of the kernel sources (csrc/*.h, csrc/*.hip, include/moc.h).  The library carries the
+    hash it was built from in moc_version(), so a measurement taken on one build can be told from a
+    measurement taken on another."""
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".hip")))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "moc.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
 
 
 def _run(cmd, verbose):
@@ -39,9 +54,11 @@ def build(verbose=True, only=None):
     """Compiles every source (or the ones named in `only`, reusing the other objects) and links."""
     os.makedirs(OBJ, exist_ok=True)
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
-    todo = [(s, o) for s, o in zip(SOURCES, objs) if only is None or s in only or not os.path.exists(o)]
+    # moc_api.hip holds the version string with the source hash, so it is compiled every time
+    todo = [(s, o) for s, o in zip(SOURCES, objs) if only is None or s in only or s == "moc_api.hip" or not os.path.exists(o)]
+    define = ['-DMOC_SOURCE_HASH="%s"' % source_hash()]
     with ThreadPoolExecutor(max_workers=4) as pool:
-        jobs = [pool.submit(_run, [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", o], verbose) for s, o in todo]
+        jobs = [pool.submit(_run, [HIPCC] + FLAGS + define + ["-c", os.path.join(CSRC, s), "-o", o], verbose) for s, o in todo]
         for j in jobs:
             j.result()
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)

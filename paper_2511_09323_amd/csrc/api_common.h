@@ -79,6 +79,8 @@ struct Options {          // environment, read once when the library is loaded
     int tile;             // MOC_GEMM_TILE=256|192|128 forces a tile shape, 0 = choose by problem size
     int decode_fused;     // MOC_DECODE_FUSED=0: grouped decode of one token as separate launches
     int decode_fused_p;   // MOC_DECODE_FUSED_P=n: workgroups of the single-launch grouped decode kernel, 0 = choose
+    int bwd_epilogue;     // MOC_BWD_EPILOGUE=1: backward pointwise step inside the dZ' GEMM's epilogue (mask + prefix tables) instead of the expansion kernel
+    int gemm_persistent;  // MOC_GEMM_PERSISTENT=0: one workgroup per GEMM tile instead of one per compute unit walking over tiles
     int decode_persistent;  // MOC_DECODE_PERSISTENT=1: row-wide decode as one persistent launch (measured slower than the separate launches)
     Options();
 };

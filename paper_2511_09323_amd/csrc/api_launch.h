@@ -16,20 +16,24 @@ namespace mocapi {
 using namespace moc;
 
 // ------------------------------------------------------------------------ GEMM dispatch
+// Workgroups of a persistent GEMM launch: one per compute unit (the kernels' LDS use allows no more),
+// or 0 (one workgroup per tile) with MOC_GEMM_PERSISTENT=0.
+inline int persistent_workgroups() { return options().gemm_persistent ? device_cu_count() : 0; }
+
 template <int BM, int BN, bool AKM, bool BKM, class Epi>
 hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t st) {
     const bool tail = pr.Kc % kMfmaBK != 0 || pr.Kc2 % kMfmaBK != 0;
     // Four wavefronts, three k-slices in flight from global memory.  Measured over the whole training step:
     // three slices beat two by 1.3 %, four give nothing more; eight wavefronts (2 x 4) are faster in
     // isolation at short contractions but 2.5 % slower over the step.
-    if (!tail) return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi, 4, 3>(pr, epi, st);
+    if (!tail) return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 0, Epi, 4, 3>(pr, epi, st, persistent_workgroups());
     if constexpr (AKM != BKM) {
         const GemmOperand<bf16_t>& kc = AKM ? pr.B : pr.A;
         const int kmax = std::max(pr.Kc, pr.Kc2);
         if (pr.kc_zero_padded && kc.ld >= round_up(kmax, kMfmaBK))
-            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 2, Epi, 4, 3>(pr, epi, st);
+            return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 2, Epi, 4, 3>(pr, epi, st, persistent_workgroups());
     }
-    return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 1, Epi, 4, 3>(pr, epi, st);
+    return launch_gemm_bf16_mfma<BM, BN, AKM, BKM, 1, Epi, 4, 3>(pr, epi, st, persistent_workgroups());
 }
 
 // Runs C = A B^T (+ second segment) with the epilogue `epi`.  AKM / BKM state the operand layouts
@@ -92,9 +96,9 @@ moc_status run_gemm_batch3(const char* name, const char* const names[3], const G
             MfmaBatch<EpiStore<E>, 3> b;
             for (int i = 0; i < 3; ++i) { b.pr[i] = pr[i]; b.epi[i] = epi[i]; }
             Span span(name, st);
-            hipError_t e = best == 0   ? launch_gemm_bf16_mfma_batch<256, 256, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st)
-                           : best == 1 ? launch_gemm_bf16_mfma_batch<256, 192, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st)
-                                       : launch_gemm_bf16_mfma_batch<128, 128, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st);
+            hipError_t e = best == 0   ? launch_gemm_bf16_mfma_batch<256, 256, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups())
+                           : best == 1 ? launch_gemm_bf16_mfma_batch<256, 192, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups())
+                                       : launch_gemm_bf16_mfma_batch<128, 128, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups());
             if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
             return MOC_OK;
         }

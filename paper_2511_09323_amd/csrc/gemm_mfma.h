@@ -111,10 +111,24 @@ __device__ __forceinline__ int xcd_contiguous_index(int g, int total) {
     return xcd * (total >> 3) + min(xcd, total & 7) + local;
 }
 
-// One output tile, workgroup-wide; `logical` is the tile's position in the band order described below.
+// What a workgroup needs to know about the tile it works on (all uniform except the two offset arrays).
+template <int LA, int LB> struct MfmaTileCtx {
+    const bf16_t *ap, *ap2, *bp, *bp2;
+    int lda, ldb, Kc, Kc2, nk0, nk;
+    int M, N, m0, n0;
+    int a_off[LA], b_off[LB];
+};
+
+// Output tiles item_first, item_first + item_stride, ... < item_total of the problems prs[0 .. ] (all of
+// one shape: tiles_m x tiles_n tiles each, problem z owning items z * tiles_m * tiles_n ...), workgroup-wide.
+// With xcd_map the item numbers are first sent through xcd_contiguous_index (item_stride must then be a
+// multiple of 8, or the workgroup has a single item).  A workgroup that has several tiles issues the
+// global loads of the next tile's first two k-slices before it writes the current tile out, so that the
+// epilogue and the next prologue overlap; one barrier separates the epilogue's use of the stage memory
+// from the next tile's staging.
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
-__device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi,
-                                                    int logical) {
+__device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, const Epi* epis, int tiles_m, int tiles_n,
+                                                     int item_first, int item_stride, int item_total, bool xcd_map) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
@@ -126,77 +140,90 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must consist of 32x32 blocks");
     constexpr int LA = TA::kChunks64 / NWV, LB = TB::kChunks64 / NWV;
     static_assert(LA >= 1 && LB >= 1, "tile too small for this many threads");
+    using Ctx = MfmaTileCtx<LA, LB>;
     extern __shared__ __align__(16) unsigned char smem[];
-    const int M = pr.M, N = pr.N;
-
-    // ---- tile order: bands of 8 tile-rows, column by column inside a band, so that a contiguous
-    //      range of tiles (one XCD's share) touches few distinct operand panels.
-    constexpr int GROUP = 8;
-    const int band = logical / (GROUP * tiles_n);
-    const int first_m = band * GROUP;
-    const int gsz = min(tiles_m - first_m, GROUP);
-    const int in_band = logical - band * GROUP * tiles_n;
-    const int m0 = (first_m + in_band % gsz) * BM;
-    const int n0 = (in_band / gsz) * BN;
+    const int nblk = tiles_m * tiles_n;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
-    // ---- staging assignment.  KC: chunk c -> (row c / 4, k chunk c % 4); rows past the edge are
-    //      clamped.  KM: chunk c -> (k row c / (ROWS/8), column chunk c % (ROWS/8)); columns past
-    //      the readable extent are clamped.  Offsets are in elements relative to (row0, k = 0).
-    int a_off[LA], a_lds[LA], a_k[LA];
-    int b_off[LB], b_lds[LB], b_k[LB];
+    // ---- staging assignment (the same for every tile).  KC: chunk c -> (row c / 4, k chunk c % 4); rows
+    //      past the edge are clamped.  KM: chunk c -> (k row c / (ROWS/8), column chunk c % (ROWS/8));
+    //      columns past the readable extent are clamped.
+    int a_lds[LA], a_k[LA], b_lds[LB], b_k[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int c = tid + i * NT;
         if (!AKM) {
-            const int row = c >> 2, ch = c & 3;
-            a_off[i] = min(m0 + row, M - 1) * (int)pr.A.ld + ch * 8;
-            a_lds[i] = kc_lds_offset(row, ch);
-            a_k[i] = ch * 8;
+            a_lds[i] = kc_lds_offset(c >> 2, c & 3);
+            a_k[i] = (c & 3) * 8;
         } else {
-            const int krow = c / (BM / 8), ch = c % (BM / 8);
-            a_off[i] = min(m0 + ch * 8, pr.A.ext - 8);
-            a_lds[i] = krow * TA::kPitch + ch * 16;
-            a_k[i] = krow;
+            a_lds[i] = (c / (BM / 8)) * TA::kPitch + (c % (BM / 8)) * 16;
+            a_k[i] = c / (BM / 8);
         }
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int c = tid + i * NT;
         if (!BKM) {
-            const int row = c >> 2, ch = c & 3;
-            b_off[i] = min(n0 + row, N - 1) * (int)pr.B.ld + ch * 8;
-            b_lds[i] = TA::kBytes + kc_lds_offset(row, ch);
-            b_k[i] = ch * 8;
+            b_lds[i] = TA::kBytes + kc_lds_offset(c >> 2, c & 3);
+            b_k[i] = (c & 3) * 8;
         } else {
-            const int krow = c / (BN / 8), ch = c % (BN / 8);
-            b_off[i] = min(n0 + ch * 8, pr.B.ext - 8);
-            b_lds[i] = TA::kBytes + krow * TB::kPitch + ch * 16;
-            b_k[i] = krow;
+            b_lds[i] = TA::kBytes + (c / (BN / 8)) * TB::kPitch + (c % (BN / 8)) * 16;
+            b_k[i] = c / (BN / 8);
         }
     }
-    const int nk0 = (pr.Kc + BK - 1) / BK;
-    const int nk = nk0 + (pr.Kc2 + BK - 1) / BK;
-    const int lda = (int)pr.A.ld, ldb = (int)pr.B.ld;
 
-    u32x4_t ga[NSETS][LA], gb[NSETS][LB];   // NSETS slices in flight from global memory
-    // global -> registers for k-slice kt (clamped to the last slice so the loop body has no branch)
-    auto fetch = [&](int buf, int kt) {
-        kt = min(kt, nk - 1);
-        const bool seg = kt >= nk0;
-        const int klen = seg ? pr.Kc2 : pr.Kc;
-        const int kwant = (seg ? kt - nk0 : kt) * BK;                                   // first k still to accumulate
-        const int kfrom = TAILMODE == 1 ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;   // first k read
-        const int klast = klen - 1 - kfrom;                                              // last valid k row of this slice
-        const bf16_t* ap = (seg ? pr.A.p2 : pr.A.p) + (AKM ? (int64_t)kfrom * lda : (int64_t)kfrom);
-        const bf16_t* bp = (seg ? pr.B.p2 : pr.B.p) + (BKM ? (int64_t)kfrom * ldb : (int64_t)kfrom);
+    // ---- tile order inside a problem: bands of 8 tile-rows, column by column inside a band, so that a
+    //      contiguous range of tiles (one XCD's share) touches few distinct operand panels.
+    auto setup = [&](Ctx& t, int item, int& z) {
+        const int mapped = xcd_map ? xcd_contiguous_index(item, item_total) : item;
+        z = mapped / nblk;
+        const int logical = mapped - z * nblk;
+        const MfmaProblem& pr = prs[z];
+        constexpr int GROUP = 8;
+        const int band = logical / (GROUP * tiles_n);
+        const int first_m = band * GROUP;
+        const int gsz = min(tiles_m - first_m, GROUP);
+        const int in_band = logical - band * GROUP * tiles_n;
+        t.M = pr.M; t.N = pr.N;
+        t.m0 = (first_m + in_band % gsz) * BM;
+        t.n0 = (in_band / gsz) * BN;
+        t.ap = pr.A.p; t.ap2 = pr.A.p2; t.bp = pr.B.p; t.bp2 = pr.B.p2;
+        t.lda = (int)pr.A.ld; t.ldb = (int)pr.B.ld;
+        t.Kc = pr.Kc; t.Kc2 = pr.Kc2;
+        t.nk0 = (pr.Kc + BK - 1) / BK;
+        t.nk = t.nk0 + (pr.Kc2 + BK - 1) / BK;
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
-            int off = a_off[i];
-            if (AKM) off += (TAILMODE ? min(a_k[i] * lda, klast * lda) : a_k[i] * lda);
+            const int c = tid + i * NT;
+            if (!AKM) t.a_off[i] = min(t.m0 + (c >> 2), t.M - 1) * t.lda + (c & 3) * 8;
+            else t.a_off[i] = min(t.m0 + (c % (BM / 8)) * 8, pr.A.ext - 8);
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int c = tid + i * NT;
+            if (!BKM) t.b_off[i] = min(t.n0 + (c >> 2), t.N - 1) * t.ldb + (c & 3) * 8;
+            else t.b_off[i] = min(t.n0 + (c % (BN / 8)) * 8, pr.B.ext - 8);
+        }
+    };
+
+    u32x4_t ga[NSETS][LA], gb[NSETS][LB];   // NSETS slices in flight from global memory
+    // global -> registers for k-slice kt of tile t (clamped to the last slice so the loop body has no branch)
+    auto fetch = [&](const Ctx& t, int buf, int kt) {
+        kt = min(kt, t.nk - 1);
+        const bool seg = kt >= t.nk0;
+        const int klen = seg ? t.Kc2 : t.Kc;
+        const int kwant = (seg ? kt - t.nk0 : kt) * BK;                                  // first k still to accumulate
+        const int kfrom = TAILMODE == 1 ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;   // first k read
+        const int klast = klen - 1 - kfrom;                                              // last valid k row of this slice
+        const bf16_t* ap = (seg ? t.ap2 : t.ap) + (AKM ? (int64_t)kfrom * t.lda : (int64_t)kfrom);
+        const bf16_t* bp = (seg ? t.bp2 : t.bp) + (BKM ? (int64_t)kfrom * t.ldb : (int64_t)kfrom);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            int off = t.a_off[i];
+            if (AKM) off += (TAILMODE ? min(a_k[i] * t.lda, klast * t.lda) : a_k[i] * t.lda);
             ga[buf][i] = *reinterpret_cast<const u32x4_t*>(ap + off);
             if (TAILMODE == 1) {
                 const int k = kfrom + a_k[i];
@@ -205,8 +232,8 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
-            int off = b_off[i];
-            if (BKM) off += (TAILMODE ? min(b_k[i] * ldb, klast * ldb) : b_k[i] * ldb);
+            int off = t.b_off[i];
+            if (BKM) off += (TAILMODE ? min(b_k[i] * t.ldb, klast * t.ldb) : b_k[i] * t.ldb);
             gb[buf][i] = *reinterpret_cast<const u32x4_t*>(bp + off);
             if (TAILMODE == 1) {
                 const int k = kfrom + b_k[i];
@@ -223,13 +250,6 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
     };
 
     f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
     constexpr int NREAD = TN * (BKM ? 2 : 1) + TM * (AKM ? 2 : 1);    // LDS reads per half slice
     bf16x8_t fm[2][TM], fn[2][TN];
     auto load_frags = [&](int buf, int stage, int kk) {
@@ -249,112 +269,153 @@ __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int t
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fn[buf][j], fm[buf][i], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: slices 0 and 1 into LDS, slices 2 .. NSETS+1 into registers
-    fetch(0, 0);
-    fetch(1, 1);
-    stash(0, 0);
-    stash(1, 1);
-#pragma unroll
-    for (int i = 0; i < NSETS; ++i) fetch(i, 2 + i);
-    __syncthreads();
-    load_frags(0, 0, 0);
-
-    int st_cur = 0, st_next = 1, st_fill = 2;
-    // One k-slice.  On entry fragment buffer 0 holds the first half of slice kt; register set
-    // `buf` holds slice kt+2.  LDS reads are issued ahead of the LDS writes in program order (the
-    // compiler cannot tell the stages apart) and everything is spread between the MFMAs.
-    auto slice = [&](auto buf_c, int kt) {
-        constexpr int buf = decltype(buf_c)::value;
-        load_frags(1, st_cur, 1);       // second half of slice kt
-        stash(buf, st_fill);            // slice kt+2 -> LDS (its stage was last read in slice kt-1)
-        mma(0);
-        fetch(buf, kt + 2 + NSETS);     // slice kt+2+NSETS -> registers
-        load_frags(0, st_next, 0);      // first half of slice kt+1 (visible since the last barrier)
-        mma(1);
-        // first half: the fragment reads go out with the first quarter of the MFMAs, the LDS writes
-        // with the rest; second half: fragment reads with the first half of the MFMAs, global loads
-        // spread over all of them (measured best of several spreads).
-        constexpr int NM = TM * TN;
-        SchedSeq<0, NM, 0, NM / 4, NREAD, NM / 4, NM, LA + LB, 0, 0, 0>::apply();
-        SchedSeq<0, NM, 0, NM / 2, NREAD, 0, 0, 0, 0, NM, LA + LB>::apply();
-        __syncthreads();
-        const int t = st_cur;
-        st_cur = st_next;
-        st_next = st_fill;
-        st_fill = t;
-    };
-    int kt = 0;
-    for (; kt + NSETS <= nk; kt += NSETS) {
-        slice(std::integral_constant<int, 0>{}, kt);
-        slice(std::integral_constant<int, 1>{}, kt + 1);
-        if constexpr (NSETS > 2) slice(std::integral_constant<int, 2>{}, kt + 2);
-        if constexpr (NSETS > 3) slice(std::integral_constant<int, 3>{}, kt + 3);
-    }
-    if (kt < nk) slice(std::integral_constant<int, 0>{}, kt++);
-    if (kt < nk) slice(std::integral_constant<int, 1>{}, kt++);
-    if constexpr (NSETS > 3)
-        if (kt < nk) slice(std::integral_constant<int, 2>{}, kt++);
-
-    // ---- epilogue.  acc[i][j][4*ii + r] is C[m, n] with m = .. + lane % 32 and n = .. + 8*ii +
-    //      4*(lane/32) + r: a lane owns 4 consecutive n of 32 different rows, which would make
-    //      scattered 8/16-byte global stores.  Each wave therefore turns its 32-row blocks around
-    //      in a private LDS area (the stages are free after the last barrier) and hands the
-    //      epilogue functor whole row segments: 32 lanes x 4 columns = 128 consecutive columns.
-    //      Wave tiles whose row segments do not divide the 64 lanes (96 columns: 24 lanes per row,
-    //      16 lanes idle) store straight from the accumulator layout instead, which measured faster
-    //      for them: 16 or 32 contiguous bytes per row and store instruction.
-    constexpr bool kDirectStores = 64 % (WN / 4) != 0;
-    if constexpr (kDirectStores) {
+    Ctx cur, nxt;
+    int zc = 0, zn = 0;
+    int item = item_first;
+    if (item >= item_total) return;
+    setup(cur, item, zc);
+    fetch(cur, 0, 0);
+    fetch(cur, 1, 1);
+    for (;;) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int ii = 0; ii < 4; ++ii) {
-                    const int m = m0 + wm0 + i * 32 + (lane & 31);
-                    const int n = n0 + wn0 + j * 32 + 8 * ii + 4 * (lane >> 5);
-                    const float v[4] = {acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
-                    if (m < M) epi.store4(m, n, v);
-                }
-    } else {
-        constexpr int EPITCH = WN * 4 + 16;                       // bytes per staged row (fp32)
-        static_assert(NWV * 32 * EPITCH <= Cfg::kLds, "epilogue staging must fit in the stage memory");
-        unsigned char* area = smem + wave * (32 * EPITCH);
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+        // ---- prologue: slices 0 and 1 (already on their way) into LDS, slices 2 .. NSETS+1 into registers
+        stash(0, 0);
+        stash(1, 1);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int ii = 0; ii < 4; ++ii) {
-                    const int col = j * 32 + 8 * ii + 4 * (lane >> 5);
-                    *reinterpret_cast<f32x4_t*>(area + (lane & 31) * EPITCH + col * 4) =
-                        f32x4_t{acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int LPR = WN / 4;                            // lanes per staged row
-            constexpr int RPI = 64 / LPR;                          // rows per instruction
-#pragma unroll 4
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int row = it * RPI + lane / LPR, c4 = lane % LPR;
-                if (64 % LPR != 0 && lane >= RPI * LPR) continue;    // lanes beyond the last whole row
-                const f32x4_t t = *reinterpret_cast<const f32x4_t*>(area + row * EPITCH + c4 * 16);
-                const int m = m0 + wm0 + i * 32 + row;
-                const float v[4] = {t[0], t[1], t[2], t[3]};
-                if (m < M) epi.store4(m, n0 + wn0 + c4 * 4, v);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int i = 0; i < NSETS; ++i) fetch(cur, i, 2 + i);
+        __syncthreads();
+        load_frags(0, 0, 0);
+
+        int st_cur = 0, st_next = 1, st_fill = 2;
+        // One k-slice.  On entry fragment buffer 0 holds the first half of slice kt; register set
+        // `buf` holds slice kt+2.  LDS reads are issued ahead of the LDS writes in program order (the
+        // compiler cannot tell the stages apart) and everything is spread between the MFMAs.
+        auto slice = [&](auto buf_c, int kt) {
+            constexpr int buf = decltype(buf_c)::value;
+            load_frags(1, st_cur, 1);       // second half of slice kt
+            stash(buf, st_fill);            // slice kt+2 -> LDS (its stage was last read in slice kt-1)
+            mma(0);
+            fetch(cur, buf, kt + 2 + NSETS);     // slice kt+2+NSETS -> registers
+            load_frags(0, st_next, 0);      // first half of slice kt+1 (visible since the last barrier)
+            mma(1);
+            // first half: the fragment reads go out with the first quarter of the MFMAs, the LDS writes
+            // with the rest; second half: fragment reads with the first half of the MFMAs, global loads
+            // spread over all of them (measured best of several spreads).
+            constexpr int NM = TM * TN;
+            SchedSeq<0, NM, 0, NM / 4, NREAD, NM / 4, NM, LA + LB, 0, 0, 0>::apply();
+            SchedSeq<0, NM, 0, NM / 2, NREAD, 0, 0, 0, 0, NM, LA + LB>::apply();
+            __syncthreads();
+            const int t = st_cur;
+            st_cur = st_next;
+            st_next = st_fill;
+            st_fill = t;
+        };
+        const int nk = cur.nk;
+        int kt = 0;
+        for (; kt + NSETS <= nk; kt += NSETS) {
+            slice(std::integral_constant<int, 0>{}, kt);
+            slice(std::integral_constant<int, 1>{}, kt + 1);
+            if constexpr (NSETS > 2) slice(std::integral_constant<int, 2>{}, kt + 2);
+            if constexpr (NSETS > 3) slice(std::integral_constant<int, 3>{}, kt + 3);
         }
+        if (kt < nk) slice(std::integral_constant<int, 0>{}, kt++);
+        if (kt < nk) slice(std::integral_constant<int, 1>{}, kt++);
+        if constexpr (NSETS > 3)
+            if (kt < nk) slice(std::integral_constant<int, 2>{}, kt++);
+
+        // ---- the next tile's first two slices go out before this tile is written
+        const int next_item = item + item_stride;
+        const bool more = next_item < item_total;
+        if (more) {
+            setup(nxt, next_item, zn);
+            fetch(nxt, 0, 0);
+            fetch(nxt, 1, 1);
+        }
+
+        // ---- epilogue.  acc[i][j][4*ii + r] is C[m, n] with m = .. + lane % 32 and n = .. + 8*ii +
+        //      4*(lane/32) + r: a lane owns 4 consecutive n of 32 different rows, which would make
+        //      scattered 8/16-byte global stores.  Each wave therefore turns its 32-row blocks around
+        //      in a private LDS area (the stages are free after the last barrier) and hands the
+        //      epilogue functor whole row segments: 32 lanes x 4 columns = 128 consecutive columns.
+        //      Wave tiles whose row segments do not divide the 64 lanes (96 columns: 24 lanes per row,
+        //      16 lanes idle) store straight from the accumulator layout instead, which measured faster
+        //      for them: 16 or 32 contiguous bytes per row and store instruction.
+        const Epi& epi = epis[zc];
+        const int M = cur.M, m0 = cur.m0, n0 = cur.n0;
+        constexpr bool kDirectStores = 64 % (WN / 4) != 0;
+        if constexpr (kDirectStores) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) {
+                        const int m = m0 + wm0 + i * 32 + (lane & 31);
+                        const int n = n0 + wn0 + j * 32 + 8 * ii + 4 * (lane >> 5);
+                        const float v[4] = {acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
+                        if (m < M) epi.store4(m, n, v);
+                    }
+        } else {
+            constexpr int EPITCH = WN * 4 + 16;                       // bytes per staged row (fp32)
+            static_assert(NWV * 32 * EPITCH <= Cfg::kLds, "epilogue staging must fit in the stage memory");
+            unsigned char* area = smem + wave * (32 * EPITCH);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) {
+                        const int col = j * 32 + 8 * ii + 4 * (lane >> 5);
+                        *reinterpret_cast<f32x4_t*>(area + (lane & 31) * EPITCH + col * 4) =
+                            f32x4_t{acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2], acc[i][j][4 * ii + 3]};
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                constexpr int LPR = WN / 4;                            // lanes per staged row
+                constexpr int RPI = 64 / LPR;                          // rows per instruction
+#pragma unroll 4
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int row = it * RPI + lane / LPR, c4 = lane % LPR;
+                    if (64 % LPR != 0 && lane >= RPI * LPR) continue;    // lanes beyond the last whole row
+                    const f32x4_t t = *reinterpret_cast<const f32x4_t*>(area + row * EPITCH + c4 * 16);
+                    const int m = m0 + wm0 + i * 32 + row;
+                    const float v[4] = {t[0], t[1], t[2], t[3]};
+                    if (m < M) epi.store4(m, n0 + wn0 + c4 * 4, v);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+        if (!more) break;
+        __syncthreads();                   // every wavefront is done with the stage memory
+        cur = nxt;
+        zc = zn;
+        item = next_item;
     }
 }
 
+// One output tile of one problem (`logical` is its position in the band order).
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
+__device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi,
+                                                    int logical) {
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(&pr, &epi, tiles_m, tiles_n, logical, 1 << 30,
+                                                                      tiles_m * tiles_n, false);
+}
+
+// The grid is either one workgroup per tile or, when there are more tiles than the chip holds workgroups,
+// a multiple of 8 workgroups that each walk over several tiles (persistent).
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi) {
-    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(pr, tiles_m, tiles_n, epi,
-                                                                     xcd_contiguous_index(blockIdx.x, tiles_m * tiles_n));
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(&pr, &epi, tiles_m, tiles_n, blockIdx.x, gridDim.x,
+                                                                      tiles_m * tiles_n, true);
 }
 
 // NB independent problems of one shape and layout in one launch (the three weight-gradient products
@@ -367,10 +428,8 @@ template <class Epi, int NB> struct MfmaBatch {
 
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatch<Epi, NB> b, int tiles_m, int tiles_n) {
-    const int nblk = tiles_m * tiles_n;
-    const int item = xcd_contiguous_index(blockIdx.x, NB * nblk);
-    const int z = item / nblk;
-    gemm_bf16_mfma_tile<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr[z], tiles_m, tiles_n, b.epi[z], item - z * nblk);
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr, b.epi, tiles_m, tiles_n, blockIdx.x, gridDim.x,
+                                                                      NB * tiles_m * tiles_n, true);
 }
 
 // Up to NB independent problems that share the output width, the contraction lengths and the layouts
@@ -422,24 +481,33 @@ inline bool mfma_problem_ok(const MfmaProblem& p) {
     return ok && operand_ok(p.A, p.M, two) && operand_ok(p.B, p.N, two);
 }
 
+// Workgroups to launch for `tiles` tiles: one per tile, or `persistent_wgs` (rounded down to a multiple of
+// 8, the number of XCDs) workgroups that walk over the tiles when there are more tiles than that.
+inline int mfma_grid(int tiles, int persistent_wgs) {
+    const int p = persistent_wgs / 8 * 8;
+    return (p >= 8 && tiles > p) ? p : tiles;
+}
+
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
-inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st) {
+inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hipStream_t st, int persistent_wgs = 0) {
     static_assert(NSETS >= 2 && NSETS <= 4, "two to four slices in flight");
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>;
     LdsAttr<gemm_bf16_mfma_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m, tiles_n, epi);
+    hipLaunchKernelGGL(kern, dim3(mfma_grid(tiles_m * tiles_n, persistent_wgs)), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m,
+                       tiles_n, epi);
     return hipGetLastError();
 }
 
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
-inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipStream_t st) {
+inline hipError_t launch_gemm_bf16_mfma_batch(const MfmaBatch<Epi, NB>& b, hipStream_t st, int persistent_wgs = 0) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     auto kern = gemm_bf16_mfma_batch_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
     LdsAttr<gemm_bf16_mfma_batch_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>, Cfg::kLds>::use();      // attribute set at library set-up
     const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(NB * tiles_m * tiles_n), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3(mfma_grid(NB * tiles_m * tiles_n, persistent_wgs)), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m,
+                       tiles_n);
     return hipGetLastError();
 }
 

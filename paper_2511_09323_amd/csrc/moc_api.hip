@@ -65,7 +65,7 @@ static int env_int(const char* name, int dflt) {
 Options::Options()
     : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)),
       decode_fused(env_int("MOC_DECODE_FUSED", 1)), decode_fused_p(env_int("MOC_DECODE_FUSED_P", 0)),
-      decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
+      bwd_epilogue(env_int("MOC_BWD_EPILOGUE", 0)), gemm_persistent(env_int("MOC_GEMM_PERSISTENT", 1)), decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
 static const Options g_options;
 const Options& options() { return g_options; }
 
@@ -260,6 +260,9 @@ const char* moc_status_string(int status) {
 
 const char* moc_last_error(void) { return g_err; }
 
-const char* moc_version(void) { return "moc-ffn 0.1 gfx950"; }
+#ifndef MOC_SOURCE_HASH
+#define MOC_SOURCE_HASH "unknown"
+#endif
+const char* moc_version(void) { return "moc-ffn 0.2 gfx950 src:" MOC_SOURCE_HASH; }
 
 }  // extern "C"

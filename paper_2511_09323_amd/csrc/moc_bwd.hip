@@ -18,7 +18,7 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     moc_status s;
     GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0, false};
     const size_t expand_lds = (size_t)3 * D.ldF * sizeof(E);
-    if (!DENSE && expand_lds <= 160 * 1024 - 64) {
+    if (!DENSE && expand_lds <= 160 * 1024 - 64 && !options().bwd_epilogue) {
         // dZ' = dD W_down^T (bp-1) stored densely, then the pointwise step (bp-2, bp-3) on the K stored
         // channels of every token, expanded to the dense-masked rows Z', dG, dU
         if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, D.F, 0}, st)) != MOC_OK) return s;

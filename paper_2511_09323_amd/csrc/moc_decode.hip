@@ -238,6 +238,12 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     const int B = D.T;
     int32_t* idx = idx_out ? idx_out : W.idx;
     moc_status s;
+    // the gather stage stages one token's x in LDS: refuse a d it cannot hold before anything is launched
+    // (the gate stage checks its own staging in its launcher, which is the first launch)
+    constexpr int NIT = 8;
+    const size_t fused_lds = (size_t)D.d * sizeof(E) + (size_t)8 * D.d * sizeof(float);
+    const bool gather_fused = D.d <= 64 * Chunk<E>::N * NIT && fused_lds <= 160 * 1024 - 64;
+    if (!gather_fused && (size_t)D.d * sizeof(E) > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
     if (gb == 0 && key_mode == 0) {
         // row-wide Top-K on the raw gate: gate, selection, up and down projection in one launch
         const DecodePlan pl = plan_persistent<E>(D, device_cu_count());
@@ -294,9 +300,7 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
         if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
     }
     const int P = decode_splits(B, D.K);
-    constexpr int NIT = 8;
-    const size_t fused_lds = (size_t)D.d * sizeof(E) + (size_t)8 * D.d * sizeof(float);
-    if (D.d <= 64 * Chunk<E>::N * NIT && fused_lds <= 160 * 1024 - 64) {
+    if (gather_fused) {
         auto kern = B > 1 ? decode_updown_kernel<E, NIT, true> : decode_updown_kernel<E, NIT, false>;
         LdsAttr<decode_updown_kernel<E, NIT, true>, kMaxDynLds>::use();
         LdsAttr<decode_updown_kernel<E, NIT, false>, kMaxDynLds>::use();
@@ -306,7 +310,6 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
     } else {
         {
             const size_t lds = (size_t)D.d * sizeof(E);
-            if (lds > 64 * 1024) return fail(MOC_ERR_UNSUPPORTED, "decode: d = %d too large", D.d);
             Span span("decode_up", st);
             const int gx = std::max(1, std::min((D.K + 3) / 4, 1024 / B));
             hipLaunchKernelGGL((decode_up_kernel<E>), dim3(gx, B), dim3(256), lds, st, x, wu, idx, W.gsel, D.d, D.K, W.z);
