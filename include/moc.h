@@ -48,7 +48,9 @@
  *    single-launch grouped decode kernel; MOC_DECODE_PERSISTENT=1 runs row-wide decode (moc_ffn_decode,
  *    moc_ffn_decode_static) as one persistent launch instead of four launches (slower on the
  *    measured shapes, kept for study); MOC_GEMM_PERSISTENT=0 launches one workgroup per GEMM tile
- *    instead of one per compute unit looping over tiles; MOC_BWD_EPILOGUE=1 applies the backward's
+ *    instead of one per compute unit looping over tiles; MOC_GEMM_STREAMK=1 lets the training products
+ *    whose whole tiles leave part of the chip idle split their work along the contraction (needs a
+ *    larger workspace; slower as measured); MOC_BWD_EPILOGUE=1 applies the backward's
  *    pointwise step in the dZ' product's epilogue instead of a kernel of its own (slower as measured).
  *    All are read once, when the library is loaded.
  */

@@ -80,6 +80,7 @@ struct Options {          // environment, read once when the library is loaded
     int decode_fused;     // MOC_DECODE_FUSED=0: grouped decode of one token as separate launches
     int decode_fused_p;   // MOC_DECODE_FUSED_P=n: workgroups of the single-launch grouped decode kernel, 0 = choose
     int bwd_epilogue;     // MOC_BWD_EPILOGUE=1: backward pointwise step inside the dZ' GEMM's epilogue (mask + prefix tables) instead of the expansion kernel
+    int gemm_streamk;     // MOC_GEMM_STREAMK=1: split GEMM work along the contraction where whole tiles leave part of the chip idle (measured slower)
     int gemm_persistent;  // MOC_GEMM_PERSISTENT=0: one workgroup per GEMM tile instead of one per compute unit walking over tiles
     int decode_persistent;  // MOC_DECODE_PERSISTENT=1: row-wide decode as one persistent launch (measured slower than the separate launches)
     Options();
@@ -126,9 +127,32 @@ struct Dims {
     }
 };
 
+// Memory for GEMMs whose work is split along the contraction: one 256 x 256 fp32 accumulator slot and one
+// word per workgroup.  Carved out of the training workspaces when the layer is large enough for such a split
+// to be chosen at all (MOC_GEMM_STREAMK=1, bf16, at least one 256 x 256 tile per workgroup in the [T, F] or
+// the 3 x [F, d] products).  The words need no initialisation.
+constexpr int kStreamKSlots = 256;
+struct StreamKArea {
+    float* part = nullptr;
+    unsigned long long* flag = nullptr;
+    template <class E> static bool wanted(const Dims& D) {
+        if (!std::is_same<E, uint16_t>::value || !options().gemm_streamk) return false;
+        const int64_t tf = (int64_t)((D.T + 255) / 256) * ((D.F + 255) / 256);
+        const int64_t fd = 3 * (int64_t)((D.F + 255) / 256) * ((D.d + 255) / 256);
+        return tf >= kStreamKSlots || fd >= kStreamKSlots;
+    }
+    template <class E> void carve(Carver& c, const Dims& D) {
+        if (!wanted<E>(D)) return;
+        part = c.take<float>((size_t)kStreamKSlots * 256 * 256);
+        flag = c.take<unsigned long long>(kStreamKSlots);
+    }
+};
+unsigned long long next_streamk_tag();
+
 template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gate, U, masked Z'
     float *G, *keys;                   // keys: transformed selection keys (Top-K position variants only)
     E *U, *Zd;
+    StreamKArea sk;
     size_t bytes;
     FwdWs(void* ws, const Dims& D, bool dense, bool keyed = false) {
         Carver c(ws);
@@ -136,6 +160,7 @@ template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gat
         U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
         Zd = c.take<E>((size_t)D.T * D.ldF);
         keys = keyed ? c.take<float>((size_t)D.T * D.ldF) : nullptr;
+        sk.carve<E>(c, D);
         bytes = c.off;
     }
 };
@@ -144,6 +169,7 @@ template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mas
     uint32_t* maskw;
     uint16_t* pref;
     E *dZd, *Zd, *dGd, *dUd;
+    StreamKArea sk;
     size_t bytes;
     BwdWs(void* ws, const Dims& D, bool dense) {
         Carver c(ws);
@@ -153,6 +179,7 @@ template <class E> struct BwdWs {      // dense [T, ldF] operands (+ the bit mas
         Zd = c.take<E>((size_t)D.T * D.ldF);
         dGd = c.take<E>((size_t)D.T * D.ldF);
         dUd = c.take<E>((size_t)D.T * D.ldF);
+        sk.carve<E>(c, D);
         bytes = c.off;
     }
 };

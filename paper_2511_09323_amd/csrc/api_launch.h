@@ -39,11 +39,27 @@ hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t s
 // Runs C = A B^T (+ second segment) with the epilogue `epi`.  AKM / BKM state the operand layouts
 // at compile time (they must match pr.A.km / pr.B.km).  bf16 problems that satisfy the MFMA
 // kernel's assumptions go to the matrix cores, everything else to the generic kernel.
+inline StreamKArgs streamk_args(const StreamKArea& a, int nk) {
+    return StreamKArgs{a.part, a.flag, next_streamk_tag(), std::max(1, nk / 8), 1 << 20};
+}
+inline int streamk_workgroups() { return std::min(persistent_workgroups(), kStreamKSlots) / 8 * 8; }
+
+// `sk`, if given and carved, lets a product whose whole tiles would leave part of the chip idle in their last
+// round split its work along the contraction instead (256 x 256 tiles, contraction a multiple of 32).
 template <class E, bool AKM, bool BKM, class Epi>
-moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, hipStream_t st) {
+moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, hipStream_t st, const StreamKArea* sk = nullptr) {
     Span span(name, st);
     if constexpr (std::is_same<E, bf16_t>::value) {
         if (!options().force_generic && mfma_problem_ok(pr)) {
+            if (sk && sk->part && options().gemm_streamk && options().tile == 0 && pr.Kc % kMfmaBK == 0 && pr.Kc2 % kMfmaBK == 0) {
+                const int64_t tiles = (int64_t)((pr.M + 255) / 256) * ((pr.N + 255) / 256);
+                const int nk = (pr.Kc + pr.Kc2) / kMfmaBK, wgs = streamk_workgroups();
+                if (streamk_pays(tiles, nk, wgs)) {
+                    hipError_t e = launch_gemm_bf16_mfma_streamk<256, 256, AKM, BKM, 0, Epi, 4, 3>(pr, epi, streamk_args(*sk, nk), wgs, st);
+                    if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+                    return MOC_OK;
+                }
+            }
             // tile shape: fewest rounds of workgroups over the 256 CUs, weighted by tile area and the
             // measured efficiency of the smaller shapes (they stage more LDS bytes per FLOP)
             struct Cand { int bm, bn; double penalty; };
@@ -75,7 +91,7 @@ moc_status run_gemm(const char* name, const GemmProblem<E>& pr, const Epi& epi, 
 // tiles of all three.
 template <class E>
 moc_status run_gemm_batch3(const char* name, const char* const names[3], const GemmProblem<E> pr[3], const EpiStore<E> epi[3],
-                           hipStream_t st) {
+                           hipStream_t st, const StreamKArea* sk = nullptr) {
     if constexpr (std::is_same<E, bf16_t>::value) {
         const bool same = pr[0].M == pr[1].M && pr[0].M == pr[2].M && pr[0].N == pr[1].N && pr[0].N == pr[2].N &&
                           pr[0].Kc == pr[1].Kc && pr[0].Kc == pr[2].Kc && pr[0].Kc % kMfmaBK == 0 && pr[0].Kc2 == 0 &&
@@ -96,6 +112,15 @@ moc_status run_gemm_batch3(const char* name, const char* const names[3], const G
             MfmaBatch<EpiStore<E>, 3> b;
             for (int i = 0; i < 3; ++i) { b.pr[i] = pr[i]; b.epi[i] = epi[i]; }
             Span span(name, st);
+            if (sk && sk->part && options().gemm_streamk && options().tile == 0) {
+                const int64_t tiles = 3 * (int64_t)((pr[0].M + 255) / 256) * ((pr[0].N + 255) / 256);
+                const int nk = pr[0].Kc / kMfmaBK, wgs = streamk_workgroups();
+                if (streamk_pays(tiles, nk, wgs)) {
+                    hipError_t e = launch_gemm_bf16_mfma_batch_streamk<256, 256, true, true, 0, EpiStore<E>, 3, 4, 3>(b, streamk_args(*sk, nk), wgs, st);
+                    if (e != hipSuccess) return fail(MOC_ERR_HIP, "%s launch: %s", name, hipGetErrorString(e));
+                    return MOC_OK;
+                }
+            }
             hipError_t e = best == 0   ? launch_gemm_bf16_mfma_batch<256, 256, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups())
                            : best == 1 ? launch_gemm_bf16_mfma_batch<256, 192, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups())
                                        : launch_gemm_bf16_mfma_batch<128, 128, true, true, 0, EpiStore<E>, 3, 4, 3>(b, st, persistent_workgroups());
@@ -104,7 +129,7 @@ moc_status run_gemm_batch3(const char* name, const char* const names[3], const G
         }
     }
     for (int i = 0; i < 3; ++i) {
-        moc_status s = run_gemm<E, true, true>(names[i], pr[i], epi[i], st);
+        moc_status s = run_gemm<E, true, true>(names[i], pr[i], epi[i], st, sk);
         if (s != MOC_OK) return s;
     }
     return MOC_OK;
@@ -114,7 +139,7 @@ moc_status run_gemm_batch3(const char* name, const char* const names[3], const G
 // with different epilogues in one launch when the MFMA kernel takes them; otherwise one run_gemm each.
 template <class E, class EpiA, class EpiB>
 moc_status run_gemm_pair(const char* name, const char* name_a, const char* name_b, const GemmProblem<E>& pa, const EpiA& ea,
-                         const GemmProblem<E>& pb, const EpiB& eb, hipStream_t st) {
+                         const GemmProblem<E>& pb, const EpiB& eb, hipStream_t st, const StreamKArea* sk = nullptr) {
     if constexpr (std::is_same<E, bf16_t>::value) {
         const bool same = pa.M == pb.M && pa.N == pb.N && pa.Kc == pb.Kc && pa.Kc % kMfmaBK == 0 && pa.Kc2 == 0 && pb.Kc2 == 0;
         if (same && !options().force_generic && mfma_problem_ok(pa) && mfma_problem_ok(pb)) {
@@ -135,9 +160,9 @@ moc_status run_gemm_pair(const char* name, const char* name_a, const char* name_
             if (options().tile == 128) best = 2;
             // worth one launch only when the two together need fewer rounds of workgroups than apart
             if (!(best_cost < 2.0 * best_single)) {
-                moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st);
+                moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st, sk);
                 if (s != MOC_OK) return s;
-                return run_gemm<E, false, false>(name_b, pb, eb, st);
+                return run_gemm<E, false, false>(name_b, pb, eb, st, sk);
             }
             Span span(name, st);
             hipError_t e = best == 0   ? launch_gemm_bf16_mfma_pair<256, 256, false, false, 0, EpiA, EpiB, 4, 3>(pa, ea, pb, eb, st)
@@ -147,9 +172,9 @@ moc_status run_gemm_pair(const char* name, const char* name_a, const char* name_
             return MOC_OK;
         }
     }
-    moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st);
+    moc_status s = run_gemm<E, false, false>(name_a, pa, ea, st, sk);
     if (s != MOC_OK) return s;
-    return run_gemm<E, false, false>(name_b, pb, eb, st);
+    return run_gemm<E, false, false>(name_b, pb, eb, st, sk);
 }
 
 // Up to NB products that differ only in their row counts (and, for weight gradients, in their

@@ -112,12 +112,59 @@ __device__ __forceinline__ int xcd_contiguous_index(int g, int total) {
 }
 
 // What a workgroup needs to know about the tile it works on (all uniform except the two offset arrays).
+// [ks, ke) is the range of k-slices of the tile that this workgroup multiplies (all of them unless the
+// work is split along k, see StreamKArgs).
 template <int LA, int LB> struct MfmaTileCtx {
     const bf16_t *ap, *ap2, *bp, *bp2;
-    int lda, ldb, Kc, Kc2, nk0, nk;
+    int lda, ldb, Kc, Kc2, nk0, nk, ks, ke;
     int M, N, m0, n0;
     int a_off[LA], b_off[LB];
 };
+
+// Splitting the work along k ("stream-K").  The k-slices of all tiles, tile after tile, form one sequence
+// of units; workgroup rank r (ranks are contiguous per XCD) takes the units [start(r), start(r + 1)), so every
+// workgroup gets the same amount of work whatever the number of tiles, and the workgroups reach their
+// epilogues at different times instead of all at once.  A tile whose slices fall to several workgroups is
+// summed along a chain that runs from its last slices to its first: a workgroup whose share does not reach the
+// end of the tile starts from the accumulators that rank r + 1 left in its slot of `part` (announced by
+// `tag` in its word of `flag`, which the reader sets back to zero) instead of from zero, and a workgroup whose
+// share does not start the tile writes its accumulators to its own slot instead of running the epilogue.  The
+// order of the additions is fixed, so results do not depend on timing.  Rank r + 1's share is the first thing it
+// does and rank r's share of the same tile the last, so in normal operation nobody waits; should the word not
+// arrive within spin_limit polls (a workgroup that the hardware has not started yet), the reader multiplies
+// the rest of the tile itself, which gives the same sum up to the order of additions.  `tag` is nonzero and
+// differs from launch to launch, and the words are left at zero, so `flag` needs no initialisation (a stale word
+// equals a fresh tag with probability 2^-64) and a captured launch can be replayed.
+struct StreamKArgs {
+    float* part;                 // one BM x BN fp32 slot per workgroup
+    unsigned long long* flag;    // one word per workgroup
+    unsigned long long tag;
+    int snap;                    // a boundary closer than this many slices to a tile boundary moves onto it
+    int spin_limit;
+};
+
+// Slot traffic goes past the caches that are not coherent across workgroups (the compute unit's L1 and,
+// between XCDs, the L2): stores are written through and loads fetched at device scope.  Fences would do as
+// well but cost far more here: a device-scope release writes back the whole L2 (which is full of freshly
+// written output tiles) and an acquire drops every clean line of the operand panels the XCD is sharing.
+// The loads are issued without waiting: a "s_waitcnt vmcnt(0)" must follow before their values are used.
+__device__ __forceinline__ void streamk_store16(unsigned char* base, uint32_t lane_off, f32x4_t v) {
+    asm volatile("global_store_dwordx4 %0, %1, %2 sc0 sc1" : : "v"(lane_off), "a"(v), "s"(base) : "memory");
+}
+__device__ __forceinline__ f32x4_t streamk_load16(const unsigned char* base, uint32_t lane_off) {
+    f32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, %2 sc0 sc1" : "=a"(v) : "v"(lane_off), "s"(base) : "memory");
+    return v;
+}
+// First unit of rank r when `units` units (nk per tile) are dealt to `ranks` workgroups.
+__device__ __forceinline__ int streamk_start(int r, int ranks, int units, int nk, int snap) {
+    if (r >= ranks) return units;
+    int s = (int)((long long)r * units / ranks);
+    const int off = s % nk;
+    if (off < snap) s -= off;
+    else if (off > nk - snap) s += nk - off;
+    return s;
+}
 
 // Output tiles item_first, item_first + item_stride, ... < item_total of the problems prs[0 .. ] (all of
 // one shape: tiles_m x tiles_n tiles each, problem z owning items z * tiles_m * tiles_n ...), workgroup-wide.
@@ -126,9 +173,10 @@ template <int LA, int LB> struct MfmaTileCtx {
 // global loads of the next tile's first two k-slices before it writes the current tile out, so that the
 // epilogue and the next prologue overlap; one barrier separates the epilogue's use of the stage memory
 // from the next tile's staging.
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS, bool SK = false>
 __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, const Epi* epis, int tiles_m, int tiles_n,
-                                                     int item_first, int item_stride, int item_total, bool xcd_map) {
+                                                     int item_first, int item_stride, int item_total, bool xcd_map,
+                                                     const StreamKArgs* sk = nullptr) {
     using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
     using TA = typename Cfg::TA;
     using TB = typename Cfg::TB;
@@ -178,7 +226,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
     // ---- tile order inside a problem: bands of 8 tile-rows, column by column inside a band, so that a
     //      contiguous range of tiles (one XCD's share) touches few distinct operand panels.
     auto setup = [&](Ctx& t, int item, int& z) {
-        const int mapped = xcd_map ? xcd_contiguous_index(item, item_total) : item;
+        const int mapped = (xcd_map && !SK) ? xcd_contiguous_index(item, item_total) : item;
         z = mapped / nblk;
         const int logical = mapped - z * nblk;
         const MfmaProblem& pr = prs[z];
@@ -195,6 +243,8 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         t.Kc = pr.Kc; t.Kc2 = pr.Kc2;
         t.nk0 = (pr.Kc + BK - 1) / BK;
         t.nk = t.nk0 + (pr.Kc2 + BK - 1) / BK;
+        t.ks = 0;
+        t.ke = t.nk;
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
             const int c = tid + i * NT;
@@ -210,9 +260,10 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
     };
 
     u32x4_t ga[NSETS][LA], gb[NSETS][LB];   // NSETS slices in flight from global memory
-    // global -> registers for k-slice kt of tile t (clamped to the last slice so the loop body has no branch)
+    // global -> registers for the kt-th k-slice of this workgroup's share of tile t (clamped to the last one so
+    // the loop body has no branch)
     auto fetch = [&](const Ctx& t, int buf, int kt) {
-        kt = min(kt, t.nk - 1);
+        kt = min(t.ks + kt, t.ke - 1);
         const bool seg = kt >= t.nk0;
         const int klen = seg ? t.Kc2 : t.Kc;
         const int kwant = (seg ? kt - t.nk0 : kt) * BK;                                  // first k still to accumulate
@@ -224,7 +275,8 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         for (int i = 0; i < LA; ++i) {
             int off = t.a_off[i];
             if (AKM) off += (TAILMODE ? min(a_k[i] * t.lda, klast * t.lda) : a_k[i] * t.lda);
-            ga[buf][i] = *reinterpret_cast<const u32x4_t*>(ap + off);
+            // uniform base + unsigned 32-bit byte offset: the load takes the base from scalar registers
+            ga[buf][i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(ap) + (uint32_t)off * 2u);
             if (TAILMODE == 1) {
                 const int k = kfrom + a_k[i];
                 if (k < kwant || k >= klen) ga[buf][i] = u32x4_t{0, 0, 0, 0};
@@ -234,7 +286,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         for (int i = 0; i < LB; ++i) {
             int off = t.b_off[i];
             if (BKM) off += (TAILMODE ? min(b_k[i] * t.ldb, klast * t.ldb) : b_k[i] * t.ldb);
-            gb[buf][i] = *reinterpret_cast<const u32x4_t*>(bp + off);
+            gb[buf][i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(bp) + (uint32_t)off * 2u);
             if (TAILMODE == 1) {
                 const int k = kfrom + b_k[i];
                 if (k < kwant || k >= klen) gb[buf][i] = u32x4_t{0, 0, 0, 0};
@@ -272,17 +324,97 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
     Ctx cur, nxt;
     int zc = 0, zn = 0;
     int item = item_first;
-    if (item >= item_total) return;
-    setup(cur, item, zc);
+    // split along k: item_first is the workgroup's number and item_stride the number of workgroups; the
+    // workgroup owns the units [u, u_end)
+    [[maybe_unused]] int rank = 0, ranks = 0, units = 0, nk_all = 0, u = 0, u_end = 0;
+    __shared__ int sk_ok;
+    auto sk_start = [&](int r) { return streamk_start(r, ranks, units, nk_all, sk->snap); };
+    // Slot of rank r.  Piece p (16 bytes per lane) of a slot lies at p * NT * 16 + tid * 16: a uniform base, which
+    // is kept opaque so that the 64 piece addresses are formed where they are used (scalar adds) rather than
+    // all ahead of the tile loop, plus one per-lane offset.
+    auto sk_slot = [&](int r) {
+        unsigned char* q = reinterpret_cast<unsigned char*>(sk->part) + (size_t)r * (BM * BN * sizeof(float));
+        asm volatile("" : "+s"(q));
+        return q;
+    };
+    auto sk_advance = [&](unsigned char*& q) {      // next piece; opaque for the same reason
+        q += NT * 16;
+        asm volatile("" : "+s"(q));
+    };
+    [[maybe_unused]] const uint32_t sk_lane = (uint32_t)tid * 16u;
+    if constexpr (SK) {
+        nk_all = (prs[0].Kc + BK - 1) / BK + (prs[0].Kc2 + BK - 1) / BK;
+        ranks = item_stride;
+        rank = xcd_contiguous_index(item_first, ranks);
+        units = item_total * nk_all;
+        u = sk_start(rank);
+        u_end = sk_start(rank + 1);
+        if (u >= u_end) return;
+        item = u / nk_all;
+        setup(cur, item, zc);
+        cur.ks = u - item * nk_all;
+        cur.ke = min(nk_all, cur.ks + (u_end - u));
+    } else {
+        if (item >= item_total) return;
+        setup(cur, item, zc);
+    }
     fetch(cur, 0, 0);
     fetch(cur, 1, 1);
     for (;;) {
+        [[maybe_unused]] bool from_slot = false;
+        if constexpr (SK) {
+            if (cur.ke < cur.nk) {
+                // the rest of this tile is rank + 1's: start from the accumulators it left (its share and whatever
+                // followed it), or take the rest over if they do not arrive
+                if (tid == 0) {
+                    int ok = 0;
+                    for (int it = 0; it < sk->spin_limit; ++it) {
+                        if (__hip_atomic_load(sk->flag + rank + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == sk->tag) {
+                            ok = 1;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(4);
+                    }
+                    sk_ok = ok;
+                }
+                __syncthreads();
+                from_slot = sk_ok != 0;
+                if (from_slot) {
+                    // all 64 loads of a lane go out before the one wait; the values are handed on only after it
+                    unsigned char* src = sk_slot(rank + 1);
+                    f32x4_t t[TM * TN * 4];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+                    for (int p = 0; p < TM * TN * 4; ++p) {
+                        t[p] = streamk_load16(src, sk_lane);
+                        sk_advance(src);
+                    }
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                    for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int ii = 0; ii < 4; ++ii) {
+                                f32x4_t v = t[(i * TN + j) * 4 + ii];
+                                asm volatile("" : "+a"(v));
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) acc[i][j][4 * ii + e] = v[e];
+                            }
+                } else {
+                    cur.ke = cur.nk;
+                }
+                __syncthreads();           // sk_ok and the slot have been read by every wavefront
+                if (from_slot && tid == 0) __hip_atomic_store(sk->flag + rank + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (!from_slot) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        }
 
         // ---- prologue: slices 0 and 1 (already on their way) into LDS, slices 2 .. NSETS+1 into registers
         stash(0, 0);
@@ -316,7 +448,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
             st_next = st_fill;
             st_fill = t;
         };
-        const int nk = cur.nk;
+        const int nk = cur.ke - cur.ks;
         int kt = 0;
         for (; kt + NSETS <= nk; kt += NSETS) {
             slice(std::integral_constant<int, 0>{}, kt);
@@ -330,10 +462,37 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
             if (kt < nk) slice(std::integral_constant<int, 2>{}, kt++);
 
         // ---- the next tile's first two slices go out before this tile is written
-        const int next_item = item + item_stride;
-        const bool more = next_item < item_total;
+        int next_item = item + item_stride;
+        bool more = next_item < item_total;
+        [[maybe_unused]] bool contributed = false;
+        if constexpr (SK) {
+            u += nk;
+            next_item = item + 1;
+            more = u < u_end;
+            if (cur.ks > 0) {
+                // a share that does not start the tile: the accumulators go to this workgroup's slot, 1 KB per
+                // store instruction, in the layout they are read back in
+                unsigned char* dst = sk_slot(rank);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii) {
+                            streamk_store16(dst, sk_lane, f32x4_t{acc[i][j][4 * ii], acc[i][j][4 * ii + 1], acc[i][j][4 * ii + 2],
+                                                                  acc[i][j][4 * ii + 3]});
+                            sk_advance(dst);
+                        }
+                // every wavefront waits until its stores have been written through, then one thread publishes
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (tid == 0) __hip_atomic_store(sk->flag + rank, sk->tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                contributed = true;
+            }
+        }
         if (more) {
             setup(nxt, next_item, zn);
+            if constexpr (SK) nxt.ke = min(nk_all, u_end - u);
             fetch(nxt, 0, 0);
             fetch(nxt, 1, 1);
         }
@@ -349,7 +508,9 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         const Epi& epi = epis[zc];
         const int M = cur.M, m0 = cur.m0, n0 = cur.n0;
         constexpr bool kDirectStores = 64 % (WN / 4) != 0;
-        if constexpr (kDirectStores) {
+        if (SK && contributed) {
+            // nothing to write: the finisher of this tile does
+        } else if constexpr (kDirectStores) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -418,6 +579,14 @@ __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_kernel(MfmaProblem pr
                                                                       tiles_m * tiles_n, true);
 }
 
+// The same with the work split along k (see StreamKArgs); the grid is a multiple of 8 workgroups, all resident.
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_streamk_kernel(MfmaProblem pr, int tiles_m, int tiles_n, Epi epi,
+                                                                          StreamKArgs sk) {
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS, true>(&pr, &epi, tiles_m, tiles_n, blockIdx.x, gridDim.x,
+                                                                            tiles_m * tiles_n, true, &sk);
+}
+
 // NB independent problems of one shape and layout in one launch (the three weight-gradient products
 // of the backward): the work items are the tiles of all problems, problem after problem.  Small
 // problems fill the chip together where each alone would not, and two launches are saved.
@@ -430,6 +599,13 @@ template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, i
 __global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_kernel(MfmaBatch<Epi, NB> b, int tiles_m, int tiles_n) {
     gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(b.pr, b.epi, tiles_m, tiles_n, blockIdx.x, gridDim.x,
                                                                       NB * tiles_m * tiles_n, true);
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+__global__ __launch_bounds__(NWV * 64) void gemm_bf16_mfma_batch_streamk_kernel(MfmaBatch<Epi, NB> b, int tiles_m, int tiles_n,
+                                                                                StreamKArgs sk) {
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS, true>(b.pr, b.epi, tiles_m, tiles_n, blockIdx.x, gridDim.x,
+                                                                            NB * tiles_m * tiles_n, true, &sk);
 }
 
 // Up to NB independent problems that share the output width, the contraction lengths and the layouts
@@ -497,6 +673,36 @@ inline hipError_t launch_gemm_bf16_mfma(const MfmaProblem& p, const Epi& epi, hi
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     hipLaunchKernelGGL(kern, dim3(mfma_grid(tiles_m * tiles_n, persistent_wgs)), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m,
                        tiles_n, epi);
+    return hipGetLastError();
+}
+
+// Whether splitting along k pays for `tiles` tiles of `nk` slices on `wgs` resident workgroups: there is at
+// least one tile per workgroup and the last round of whole tiles would leave more than 7 % of the chip idle.
+inline bool streamk_pays(int64_t tiles, int nk, int wgs) {
+    if (wgs < 8 || tiles < wgs || nk < 16 || tiles * nk >= (1ll << 30)) return false;
+    const int64_t rounds = (tiles + wgs - 1) / wgs;
+    return (double)tiles / (double)(rounds * wgs) < 0.93;
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV = 4, int NSETS = 2>
+inline hipError_t launch_gemm_bf16_mfma_streamk(const MfmaProblem& p, const Epi& epi, const StreamKArgs& sk, int wgs,
+                                                hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_streamk_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>;
+    LdsAttr<gemm_bf16_mfma_streamk_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>, Cfg::kLds>::use();
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(wgs / 8 * 8), dim3(NWV * 64), Cfg::kLds, st, p, tiles_m, tiles_n, epi, sk);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NB, int NWV = 4, int NSETS = 2>
+inline hipError_t launch_gemm_bf16_mfma_batch_streamk(const MfmaBatch<Epi, NB>& b, const StreamKArgs& sk, int wgs,
+                                                      hipStream_t st) {
+    using Cfg = MfmaCfg<BM, BN, AKM, BKM>;
+    auto kern = gemm_bf16_mfma_batch_streamk_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>;
+    LdsAttr<gemm_bf16_mfma_batch_streamk_kernel<BM, BN, AKM, BKM, TAILMODE, Epi, NB, NWV, NSETS>, Cfg::kLds>::use();
+    const int tiles_m = (b.pr[0].M + BM - 1) / BM, tiles_n = (b.pr[0].N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(wgs / 8 * 8), dim3(NWV * 64), Cfg::kLds, st, b, tiles_m, tiles_n, sk);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@
 // are in moc_fwd.hip, moc_bwd.hip and moc_decode.hip.  No device memory is allocated anywhere.
 #include <atomic>
 #include <mutex>
+#include <random>
 #include <string>
 #include <vector>
 
@@ -65,9 +66,19 @@ static int env_int(const char* name, int dflt) {
 Options::Options()
     : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)),
       decode_fused(env_int("MOC_DECODE_FUSED", 1)), decode_fused_p(env_int("MOC_DECODE_FUSED_P", 0)),
-      bwd_epilogue(env_int("MOC_BWD_EPILOGUE", 0)), gemm_persistent(env_int("MOC_GEMM_PERSISTENT", 1)), decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
+      bwd_epilogue(env_int("MOC_BWD_EPILOGUE", 0)), gemm_streamk(env_int("MOC_GEMM_STREAMK", 0)), gemm_persistent(env_int("MOC_GEMM_PERSISTENT", 1)), decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
 static const Options g_options;
 const Options& options() { return g_options; }
+
+// Tags of the split GEMM launches: a counter from a random start, scrambled (splitmix64), never zero.
+unsigned long long next_streamk_tag() {
+    static std::atomic<unsigned long long> counter{((unsigned long long)std::random_device{}() << 32) ^ std::random_device{}()};
+    unsigned long long z = counter.fetch_add(0x9E3779B97F4A7C15ull, std::memory_order_relaxed) + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z | 1ull;
+}
 
 // ------------------------------------------------------------------- per-device set-up
 // Done once per device, by the first entry point called with that device current (or by moc_init):

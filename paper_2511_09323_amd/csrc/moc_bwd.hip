@@ -21,7 +21,7 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     if (!DENSE && expand_lds <= 160 * 1024 - 64 && !options().bwd_epilogue) {
         // dZ' = dD W_down^T (bp-1) stored densely, then the pointwise step (bp-2, bp-3) on the K stored
         // channels of every token, expanded to the dense-masked rows Z', dG, dU
-        if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, D.F, 0}, st)) != MOC_OK) return s;
+        if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, D.F, 0}, st, &W.sk)) != MOC_OK) return s;
         auto kern = bwd_expand_kernel<E>;
         LdsAttr<bwd_expand_kernel<E>, kMaxDynLds>::use();
         Span span("bwd_pointwise_expand", st);
@@ -48,7 +48,7 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
         {km_operand<E>(W.dUd, D.ldF, D.ldF), km_operand<E>(x, D.d, D.d), D.F, D.d, D.T, 0, false}};
     const EpiStore<E> ew[3] = {{dwd, D.d, D.d, 0}, {dwg, D.d, D.d, 0}, {dwu, D.d, D.d, 0}};
     static const char* const wnames[3] = {"gemm_dwd", "gemm_dwg", "gemm_dwu"};
-    if ((s = run_gemm_batch3<E>("gemm_dw3", wnames, pw, ew, st)) != MOC_OK) return s;
+    if ((s = run_gemm_batch3<E>("gemm_dw3", wnames, pw, ew, st, &W.sk)) != MOC_OK) return s;
     // dX = dG W_gate^T + dU W_up^T (bp-5): one GEMM over the concatenated contraction
     GemmProblem<E> px{kc_operand<E>(W.dGd, D.ldF, W.dUd), km_operand<E>(wg, D.d, D.d, wu), D.T, D.d, D.F, D.F, true};
     return run_gemm<E, false, true>("gemm_dx", px, EpiStore<E>{dx, D.d, D.d, 0}, st);

@@ -19,7 +19,7 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
     GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0, false};
     GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0, false};
     if ((s = run_gemm_pair<E>("gemm_gate_up", "gemm_gate", "gemm_up", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, pu,
-                              EpiStore<E>{W.U, D.ldF, D.F, 0}, st)) != MOC_OK)
+                              EpiStore<E>{W.U, D.ldF, D.F, 0}, st, &W.sk)) != MOC_OK)
         return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF, nullptr};

@@ -414,6 +414,39 @@ def run_decode_reuse_case(B, d, F, K):
         assert not (7 in s and 3 not in s) and not (F - 1 in s and 7 not in s)
 
 
+def test_gemms_split_along_the_contraction():
+    """MOC_GEMM_STREAMK=1 (read once per process, hence the child process) lets the products whose whole tiles
+    would leave part of the chip idle in their last round split their work along the contraction: workgroups
+    hand partial accumulators to each other through the workspace.  Same oracle checks as the default path at
+    the 1B shape (gate, up, dZ' and the three weight gradients take the split) and at a shape with 17 k-slices
+    and ragged edges; twice on one workspace filled with junk (the words the workgroups signal through need no
+    initialisation and are left clean), bit-identical."""
+    import os
+    import subprocess
+    code = ("import torch\n"
+            "import tests.test_gpu_parity as t\n"
+            "from paper_2511_09323_amd.configs import CONFIGS\n"
+            "import paper_2511_09323_amd as moc\n"
+            "c = CONFIGS['cfg2']\n"
+            "t.run_fwd_bwd_case('cfg2-split', 2, c.T, c.d, c.F, c.K, 'bf16', expect_window_rows=40)\n"
+            "t.run_fwd_bwd_case('ragged-split', 93, 8100, 544, 2500, 300, 'bf16')\n"
+            "L = t.inputs.make_layer(93, 8100, 544, 2500, 'bf16')\n"
+            "G = t.gpu_layer(L, 'bf16')\n"
+            "ws = torch.empty(moc.workspace_bytes(8100, 544, 2500, 300, torch.bfloat16, 0), dtype=torch.uint8, device='cuda')\n"
+            "ws.fill_(0x5A)\n"
+            "outs = []\n"
+            "for rep in range(3):\n"
+            "    y, idx, gv, uv = moc.moc_ffn_fwd(G['x'], G['wg'], G['wu'], G['wd'], 300, ws=ws)\n"
+            "    torch.cuda.synchronize()\n"
+            "    outs.append((y.clone(), idx.clone()))\n"
+            "assert all(torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1]) for o in outs)\n"
+            "print('ok')\n")
+    env = dict(os.environ, MOC_GEMM_STREAMK="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
+
+
 def test_generic_kernels_serve_bf16_when_forced():
     """MOC_FORCE_GENERIC=1 (read once per process, hence the child process) routes every bf16 GEMM to the
     fp32-FMA kernel and decode to its non-MFMA kernels; results must still match the oracle."""
