@@ -29,7 +29,7 @@ template <class OutT> struct EpiStore {
         OutT* row = C + (int64_t)m * ldc;
         if (n0 + 3 < N && (ldc & 3) == 0) {
             store_vec4<OutT>(row + n0, v);
-        } else {
+        } else if (n0 < N || n0 < pad_to) {      // (a tile that hangs over the edge has whole wavefronts out here)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 int n = n0 + r;

@@ -16,12 +16,13 @@ moc_status bwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                     hipStream_t st) {
     BwdWs<E> W(ws, D, DENSE);
     moc_status s;
+    const int Fs = round_up(D.F, 4);      // whole 4-column groups into the padded [T, ldF] array (its padding is never read)
     GemmProblem<E> pz{kc_operand<E>(dy, D.d), kc_operand<E>(wd, D.d), D.T, D.F, D.d, 0, false};
     const size_t expand_lds = (size_t)3 * D.ldF * sizeof(E);
     if (!DENSE && expand_lds <= 160 * 1024 - 64 && !options().bwd_epilogue) {
         // dZ' = dD W_down^T (bp-1) stored densely, then the pointwise step (bp-2, bp-3) on the K stored
         // channels of every token, expanded to the dense-masked rows Z', dG, dU
-        if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, D.F, 0}, st, &W.sk)) != MOC_OK) return s;
+        if ((s = run_gemm<E, false, false>("gemm_dz", pz, EpiStore<E>{W.dZd, D.ldF, Fs, 0}, st, &W.sk)) != MOC_OK) return s;
         auto kern = bwd_expand_kernel<E>;
         LdsAttr<bwd_expand_kernel<E>, kMaxDynLds>::use();
         Span span("bwd_pointwise_expand", st);
@@ -67,6 +68,7 @@ moc_status bwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const 
                             void* ws, hipStream_t st) {
     BwdWs<E> W(ws, D, false);
     const int64_t wsz = (int64_t)D.F * D.d;
+    const int Fs = round_up(D.F, 4);      // whole 4-column groups into the padded [T, ldF] array (its padding is never read)
     const size_t expand_lds = (size_t)3 * D.ldF * sizeof(E);
     if (expand_lds > 160 * 1024 - 64) return fail(MOC_ERR_UNSUPPORTED, "F = %d too large for the expert backward", D.F);
     GemmProblem<E> pr[3 * kMaxExperts];
@@ -75,7 +77,7 @@ moc_status bwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const 
     for (int e = 0; e < n_exp; ++e) {
         const int64_t r0 = off[e];
         pr[e] = GemmProblem<E>{kc_operand<E>(dy + r0 * D.d, D.d), kc_operand<E>(wd + e * wsz, D.d), off[e + 1] - off[e], D.F, D.d, 0, false};
-        ee[e] = EpiStore<E>{W.dZd + r0 * D.ldF, D.ldF, D.F, 0};
+        ee[e] = EpiStore<E>{W.dZd + r0 * D.ldF, D.ldF, Fs, 0};
     }
     if ((s = run_gemm_grouped<E, false, false, EpiStore<E>, kMaxExperts>("gemm_dz_experts", n_exp, pr, ee, st)) != MOC_OK) return s;
     {

@@ -14,12 +14,16 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                     E* uvals, void* ws, hipStream_t st, int ga = 0, int gb = 0, int key_mode = 0) {
     FwdWs<E> W(ws, D, false, key_mode != 0);
     moc_status s;
+    // Columns stored by the products that fill [T, ldF] scratch arrays: F rounded up to a whole 4-column group.
+    // The up to three extra columns land in the arrays' padding, which nothing reads; without them every
+    // row would end in a partly filled group, whose element-wise stores cost about 10 us per product at the 1B shape.
+    const int Fs = round_up(D.F, 4);
     // G = X W_gate, kept in fp32 for the selection (Eq. MoC-1)
     // and U = X W_up (Eq. MoC-1): one launch for both when possible
     GemmProblem<E> pg{kc_operand<E>(x, D.d), kc_operand<E>(wg, D.d), D.T, D.F, D.d, 0, false};
     GemmProblem<E> pu{kc_operand<E>(x, D.d), kc_operand<E>(wu, D.d), D.T, D.F, D.d, 0, false};
-    if ((s = run_gemm_pair<E>("gemm_gate_up", "gemm_gate", "gemm_up", pg, EpiStore<float>{W.G, D.ldF, D.F, 0}, pu,
-                              EpiStore<E>{W.U, D.ldF, D.F, 0}, st, &W.sk)) != MOC_OK)
+    if ((s = run_gemm_pair<E>("gemm_gate_up", "gemm_gate", "gemm_up", pg, EpiStore<float>{W.G, D.ldF, Fs, 0}, pu,
+                              EpiStore<E>{W.U, D.ldF, Fs, 0}, st, &W.sk)) != MOC_OK)
         return s;
     // M = TopK(G); stored set; Z' = SiLU(G) . M . U (Eq. MoC-2)
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF, nullptr};
@@ -49,6 +53,7 @@ moc_status fwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const 
                             E* y, int32_t* idx, E* gvals, E* uvals, void* ws, hipStream_t st) {
     FwdWs<E> W(ws, D, false);
     const int64_t wsz = (int64_t)D.F * D.d;
+    const int Fs = round_up(D.F, 4);      // see fwd_impl
     GemmProblem<E> pr[kMaxExperts];
     EpiStore<float> eg[kMaxExperts];
     EpiStore<E> ee[kMaxExperts];
@@ -56,13 +61,13 @@ moc_status fwd_experts_impl(const Dims& D, int n_exp, const int32_t* off, const 
     for (int e = 0; e < n_exp; ++e) {
         const int64_t r0 = off[e];
         pr[e] = GemmProblem<E>{kc_operand<E>(x + r0 * D.d, D.d), kc_operand<E>(wg + e * wsz, D.d), off[e + 1] - off[e], D.F, D.d, 0, false};
-        eg[e] = EpiStore<float>{W.G + r0 * D.ldF, D.ldF, D.F, 0};
+        eg[e] = EpiStore<float>{W.G + r0 * D.ldF, D.ldF, Fs, 0};
     }
     if ((s = run_gemm_grouped<E, false, false, EpiStore<float>, kMaxExperts>("gemm_gate_experts", n_exp, pr, eg, st)) != MOC_OK) return s;
     for (int e = 0; e < n_exp; ++e) {
         const int64_t r0 = off[e];
         pr[e].B = kc_operand<E>(wu + e * wsz, D.d);
-        ee[e] = EpiStore<E>{W.U + r0 * D.ldF, D.ldF, D.F, 0};
+        ee[e] = EpiStore<E>{W.U + r0 * D.ldF, D.ldF, Fs, 0};
     }
     if ((s = run_gemm_grouped<E, false, false, EpiStore<E>, kMaxExperts>("gemm_up_experts", n_exp, pr, ee, st)) != MOC_OK) return s;
     TopkArgs<E> a{W.G, D.ldF, D.F, D.K, idx, nullptr, gvals, W.U, D.ldF, uvals, W.Zd, D.ldF, nullptr};
