@@ -51,7 +51,9 @@
  *    instead of one per compute unit looping over tiles; MOC_GEMM_STREAMK=1 lets the training products
  *    whose whole tiles leave part of the chip idle split their work along the contraction (needs a
  *    larger workspace; slower as measured); MOC_BWD_EPILOGUE=1 applies the backward's
- *    pointwise step in the dZ' product's epilogue instead of a kernel of its own (slower as measured).
+ *    pointwise step in the dZ' product's epilogue instead of a kernel of its own (slower as measured);
+ *    MOC_GROUPED_SPARSE=1 runs the down projection of moc_ffn_fwd_grouped with a <= 2 on the
+ *    structured-sparse matrix instruction (bf16; needs a larger workspace; not faster as measured).
  *    All are read once, when the library is loaded.
  */
 #ifndef MOC_H

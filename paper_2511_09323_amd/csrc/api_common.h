@@ -80,6 +80,7 @@ struct Options {          // environment, read once when the library is loaded
     int decode_fused;     // MOC_DECODE_FUSED=0: grouped decode of one token as separate launches
     int decode_fused_p;   // MOC_DECODE_FUSED_P=n: workgroups of the single-launch grouped decode kernel, 0 = choose
     int bwd_epilogue;     // MOC_BWD_EPILOGUE=1: backward pointwise step inside the dZ' GEMM's epilogue (mask + prefix tables) instead of the expansion kernel
+    int grouped_sparse;   // MOC_GROUPED_SPARSE=1: down projection of MoC_{a:b}, a <= 2, on the structured-sparse matrix instruction (not faster as measured)
     int gemm_streamk;     // MOC_GEMM_STREAMK=1: split GEMM work along the contraction where whole tiles leave part of the chip idle (measured slower)
     int gemm_persistent;  // MOC_GEMM_PERSISTENT=0: one workgroup per GEMM tile instead of one per compute unit walking over tiles
     int decode_persistent;  // MOC_DECODE_PERSISTENT=1: row-wide decode as one persistent launch (measured slower than the separate launches)
@@ -152,6 +153,8 @@ unsigned long long next_streamk_tag();
 template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gate, U, masked Z'
     float *G, *keys;                   // keys: transformed selection keys (Top-K position variants only)
     E *U, *Zd;
+    uint16_t* zc;                      // compressed Z' of the structured-sparse down projection (MOC_GROUPED_SPARSE=1, bf16)
+    uint32_t* zi;
     StreamKArea sk;
     size_t bytes;
     FwdWs(void* ws, const Dims& D, bool dense, bool keyed = false) {
@@ -160,6 +163,9 @@ template <class E> struct FwdWs {      // dense scratch of the forward: fp32 gat
         U = dense ? nullptr : c.take<E>((size_t)D.T * D.ldF);
         Zd = c.take<E>((size_t)D.T * D.ldF);
         keys = keyed ? c.take<float>((size_t)D.T * D.ldF) : nullptr;
+        const bool sparse = !dense && std::is_same<E, uint16_t>::value && options().grouped_sparse;
+        zc = sparse ? c.take<uint16_t>((size_t)D.T * (D.ldF / 2)) : nullptr;
+        zi = sparse ? c.take<uint32_t>((size_t)D.T * (D.ldF / 32)) : nullptr;
         sk.carve<E>(c, D);
         bytes = c.off;
     }

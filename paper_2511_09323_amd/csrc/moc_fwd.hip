@@ -2,6 +2,7 @@
 // variants and the stand-alone row selections: kernel sequences and their C entry points.
 #include "api_common.h"
 #include "api_launch.h"
+#include "gemm_sparse.h"
 
 using namespace moc;
 using namespace mocapi;
@@ -39,6 +40,24 @@ moc_status fwd_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E
                                   : run_topk<E, 256, true>("topk_select_act", a, D.T, st);
     else s = run_group_select<E, true>("group_select_act", a, D.T, ga, gb, st);      // MoC_{a:b}
     if (s != MOC_OK) return s;
+    if constexpr (std::is_same<E, bf16_t>::value) {
+        // MoC_{a:b} with a <= 2 leaves at most two nonzeros in every aligned group of four channels: on request the
+        // down projection takes the compressed Z' and the structured-sparse matrix instruction
+        if (gb != 0 && ga <= 2 && W.zc && !options().force_generic && D.d % 8 == 0 && aligned16(wd) && aligned16(y)) {
+            {
+                Span span("sparse_compress", st);
+                const int64_t n = (int64_t)D.T * (D.ldF / 32);
+                hipLaunchKernelGGL(sparse_compress_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, W.Zd, (int64_t)D.ldF,
+                                   D.T, W.zc, W.zi);
+                HIP_TRY(hipGetLastError());
+            }
+            Span span("gemm_down_sparse", st);
+            SparseDownProblem sp{W.zc, W.zi, D.ldF / 2, D.ldF / 32, wd, D.d, D.d, D.T, D.d, D.ldF, D.F};
+            hipError_t e = launch_gemm_sparse_down(sp, EpiStore<E>{y, D.d, D.d, 0}, st);
+            if (e != hipSuccess) return fail(MOC_ERR_HIP, "gemm_down_sparse launch: %s", hipGetErrorString(e));
+            return MOC_OK;
+        }
+    }
     return down_projection<E>(D, W.Zd, wd, y, st);
 }
 

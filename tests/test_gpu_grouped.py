@@ -166,3 +166,47 @@ def test_grouped_decode_separate_launches_match_too(B, a, monkeypatch):
     # the gate+select / gather / reduce launches that batches above four (and other a:b) use
     monkeypatch.setenv("MOC_DECODE_FUSED", "0")
     run_grouped_decode("unfused", 97, B, 1024, 2048, a, 8, "bf16")
+
+
+def test_grouped_forward_on_the_structured_sparse_instruction():
+    """MOC_GROUPED_SPARSE=1 (read once per process, hence the child process) sends the down projection of
+    MoC_{a:b} with a <= 2 through the compressed Z' and the structured-sparse matrix instruction.  Same
+    oracle checks as the default path: 2:8 at cfg1's shape and at the 1B shape, 1:8, 2:4 and 1:16 on small and
+    ragged shapes (a single kept value per group of four, empty groups, T and d that do not fill a tile),
+    and a 3:16 case that must quietly take the dense path."""
+    import os
+    import subprocess
+    code = ("import tests.test_gpu_grouped as t\n"
+            "from paper_2511_09323_amd.configs import CONFIGS\n"
+            "c = CONFIGS['cfg1']\n"
+            "t.run_grouped_fwd_bwd('cfg1-sparse', 1, c.T, c.d, c.F, 2, 8, 'bf16', bwd=False)\n"
+            "for T, d, F, a, b in ((100, 96, 200, 1, 4), (300, 264, 1000, 2, 8), (77, 128, 64, 1, 8), (513, 512, 1376, 2, 4),\n"
+            "                      (40, 72, 320, 1, 16), (33, 128, 96, 3, 16)):\n"
+            "    t.run_grouped_fwd_bwd('small-sparse', 95, T, d, F, a, b, 'bf16', bwd=False)\n"
+            "c = CONFIGS['cfg2']\n"
+            "t.run_grouped_fwd_bwd('cfg2-like-sparse', 2, c.T, c.d, 5464, 2, 8, 'bf16', bwd=False)\n"
+            "print('ok')\n")
+    env = dict(os.environ, MOC_GROUPED_SPARSE="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
+    assert "gemm_down_sparse" in _kernel_names_with_sparse_enabled(root, env)
+
+
+def _kernel_names_with_sparse_enabled(root, env):
+    """Names of the kernels a grouped 2:8 forward launches in a child process with `env` (from the library's own
+    per-launch timing), to make sure the request is honoured and not silently served by the dense kernel."""
+    import subprocess
+    code = ("import torch\n"
+            "import paper_2511_09323_amd as moc\n"
+            "from paper_2511_09323_amd import inputs\n"
+            "from tests import parity as P\n"
+            "L = inputs.make_layer(95, 300, 264, 1000, 'bf16')\n"
+            "G = {k: P.to_dev(v, 'bf16') for k, v in L.items()}\n"
+            "moc.timing_enable(True)\n"
+            "moc.moc_ffn_fwd_grouped(G['x'], G['wg'], G['wu'], G['wd'], 2, 8)\n"
+            "torch.cuda.synchronize()\n"
+            "print(' '.join(moc.timing_read().keys()))\n")
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    return r.stdout
