@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--no-stack", action="store_true")
     ap.add_argument("--no-grouped", action="store_true", help="skip the MoC 2:8 (grouped Top-K) legs")
     ap.add_argument("--no-experts", action="store_true", help="skip the MoC-in-MoE-experts leg")
+    ap.add_argument("--no-dense-decode", action="store_true", help="skip the dense FFN (K = d_ff) decode comparison")
     ap.add_argument("--no-small", action="store_true", help="skip the cfg0 (fp32 forward) and cfg1 (small fwd+bwd) legs")
     ap.add_argument("--no-clocks", action="store_true",
                     help="do not start rocm-smi after the run (a child process of a profiled run is refused on the GPU boxes)")
@@ -247,7 +248,8 @@ def main():
     decode = None
     if not args.no_decode:
         decode = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev)
-        decode["dense_K_equals_F"] = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, dense=True)["batches"]
+        if not args.no_dense_decode:
+            decode["dense_K_equals_F"] = decode_leg(torch, moc, inputs, CONFIGS["cfg3"], DECODE_BATCHES, dev, dense=True)["batches"]
         if roofline is not None:
             roofline["entries"] += [
                 {"kernel": "moc_ffn_decode, whole call, B=%d" % b["B"], "bound": "hbm", "achieved": b["effective_GBs"],

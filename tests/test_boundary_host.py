@@ -145,3 +145,40 @@ def test_committed_traffic_summary_has_the_roofline_kernel():
     assert ent["hbm_read_bytes"] > 0 and ent["hbm_written_bytes"] > 0
     src = open(os.path.join(ROOT, "bench.py")).read()
     assert "gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>" in src
+
+
+def test_bench_reports_committed_traffic_only_for_the_sources_it_was_measured_on(tmp_path, monkeypatch):
+    """bench.py's roofline `traffic` comes from the committed rocprofv3 counter summary.  It must be null unless
+    that summary names the hash of the kernel sources in this tree AND the loaded library was built from them."""
+    import json
+    import bench
+    from paper_2511_09323_amd.build import source_hash
+    here = source_hash()
+    assert len(here) == 16 and here == source_hash()          # a pure function of the source files
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    key = "gemm_bf16_mfma<256,256,KC,KC,tail0,EpiStore<float>>"
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+
+    def write(h):
+        (prof / "cfg2_traffic.json").write_text(json.dumps({key: {"hbm_read_bytes": 100, "hbm_written_bytes": 23}, "_source_hash": h}))
+
+    write(here)
+    val, why = bench.committed_traffic(key, "moc-ffn 0.2 gfx950 src:" + here)
+    assert val == 123 and here in why
+    val, why = bench.committed_traffic(key, "moc-ffn 0.2 gfx950 src:0000000000000000")
+    assert val is None and "not built from these sources" in why
+    val, why = bench.committed_traffic("some_other_kernel", "moc-ffn 0.2 gfx950 src:" + here)
+    assert val is None
+    write("feedfeedfeedfeed")
+    val, why = bench.committed_traffic(key, "moc-ffn 0.2 gfx950 src:" + here)
+    assert val is None and "other sources" in why
+    (prof / "cfg2_traffic.json").unlink()
+    val, why = bench.committed_traffic(key, "moc-ffn 0.2 gfx950 src:" + here)
+    assert val is None
+
+
+def test_library_version_names_the_sources_it_was_built_from(lib):
+    import re
+    v = lib.moc_version().decode()
+    assert re.search(r"src:[0-9a-f]{16}$", v), v
