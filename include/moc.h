@@ -45,7 +45,9 @@
  *    MOC_FORCE_GENERIC=1 sends every GEMM to the generic fp32-FMA kernel and decode to
  *    its non-MFMA kernels; MOC_GEMM_TILE=256|192|128 forces an MFMA tile shape;
  *    MOC_DECODE_FUSED=0 and MOC_DECODE_FUSED_P=n switch off, or set the workgroup count of, the
- *    single-launch grouped decode kernel; MOC_DECODE_PERSISTENT=1 runs row-wide decode (moc_ffn_decode,
+ *    single-launch grouped decode kernel; MOC_DECODE_SELECT_GATHER=1 repeats the selection of row-wide
+ *    decode inside every gather workgroup instead of giving it a launch of its own (not faster as
+ *    measured); MOC_DECODE_PERSISTENT=1 runs row-wide decode (moc_ffn_decode,
  *    moc_ffn_decode_static) as one persistent launch instead of four launches (slower on the
  *    measured shapes, kept for study); MOC_GEMM_PERSISTENT=0 launches one workgroup per GEMM tile
  *    instead of one per compute unit looping over tiles; MOC_GEMM_STREAMK=1 lets the training products

@@ -7,6 +7,7 @@
 
 #include "decode_kernels.h"
 #include "decode_persist.h"
+#include "decode_select_gather.h"
 
 using namespace moc;
 using namespace mocapi;
@@ -231,6 +232,28 @@ moc_status decode_persistent(const DecodePlan& pl, const Dims& D, const DecodeWs
 
 // ga:gb = 0:0 is the row-wide Top-K; otherwise the grouped selection of MoC_{a:b}, which is decided
 // inside the gate kernel (a group's channels meet in one workgroup) and needs no selection launch.
+// Selection + gather of row-wide decode in one launch (decode_select_gather.h).
+constexpr int kSelectGatherMaxLds = 156 * 1024;
+template <class E, int NCH>
+moc_status launch_select_gather_nch(const Dims& D, const E* x, const E* wu, const E* wd, const float* g, int32_t* idx, float* part,
+                                    int P, hipStream_t st) {
+    constexpr int NIT = 8;
+    auto kern = decode_select_gather_kernel<E, NIT, NCH>;
+    LdsAttr<decode_select_gather_kernel<E, NIT, NCH>, kSelectGatherMaxLds>::use();      // (the kernel has 160 bytes of static LDS)
+    Span span("decode_select_gather", st);
+    hipLaunchKernelGGL(kern, dim3(P * D.T), dim3(512), decode_select_gather_lds<E>(D.d), st, x, wu, wd, g, (int64_t)D.ldF, D.F, D.d,
+                       D.K, P, D.T, idx, part);
+    HIP_TRY(hipGetLastError());
+    return MOC_OK;
+}
+template <class E>
+moc_status launch_select_gather(const Dims& D, const E* x, const E* wu, const E* wd, const float* g, int32_t* idx, float* part, int P,
+                                hipStream_t st) {
+    if (D.F <= 2 * 2048) return launch_select_gather_nch<E, 2>(D, x, wu, wd, g, idx, part, P, st);
+    if (D.F <= 6 * 2048) return launch_select_gather_nch<E, 6>(D, x, wu, wd, g, idx, part, P, st);
+    return launch_select_gather_nch<E, 16>(D, x, wu, wd, g, idx, part, P, st);
+}
+
 template <class E>
 moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, const E* wd, E* y, int32_t* idx_out,
                        void* ws, hipStream_t st, int ga = 0, int gb = 0, int key_mode = 0) {
@@ -290,6 +313,17 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
         else s = decode_gate_group_b<E, 16>(D, x, wg, ga, gb, idx, W.gsel, st);
     }
     if (s != MOC_OK) return s;
+    const int P = decode_splits(B, D.K);
+    if (gb == 0 && key_mode == 0 && gather_fused && options().decode_select_gather && (D.F + P - 1) / P <= kDsgMaxRange &&
+        decode_select_gather_lds<E>(D.d) <= (size_t)kSelectGatherMaxLds) {
+        // selection and gather in one launch: every workgroup finds its token's threshold itself
+        if ((s = launch_select_gather<E>(D, x, wu, wd, W.g, idx, W.part, P, st)) != MOC_OK) return s;
+        Span span("decode_reduce", st);
+        const int64_t n = (int64_t)B * D.d;
+        hipLaunchKernelGGL((decode_reduce_kernel<E>), dim3((unsigned)((n + 63) / 64)), dim3(1024), 0, st, W.part, P, n, y);
+        HIP_TRY(hipGetLastError());
+        return MOC_OK;
+    }
     if (gb == 0) {
         TopkArgs<float> a{W.g, D.ldF, D.F, D.K, idx, W.gsel, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr};
         if (key_mode != 0) {
@@ -299,7 +333,6 @@ moc_status decode_impl(const Dims& D, const E* x, const E* wg, const E* wu, cons
         }
         if ((s = run_topk<float, 1024, false>("decode_topk", a, B, st)) != MOC_OK) return s;
     }
-    const int P = decode_splits(B, D.K);
     if (gather_fused) {
         auto kern = B > 1 ? decode_updown_kernel<E, NIT, true> : decode_updown_kernel<E, NIT, false>;
         LdsAttr<decode_updown_kernel<E, NIT, true>, kMaxDynLds>::use();

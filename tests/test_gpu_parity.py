@@ -384,6 +384,32 @@ def test_persistent_single_launch_decode():
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
 
 
+def test_decode_with_the_selection_inside_the_gather_launch():
+    """MOC_DECODE_SELECT_GATHER=1 (read once per process, hence the child process): every gather workgroup of
+    row-wide decode finds its token's Top-K threshold itself, so the selection needs no launch of its own.  Same
+    oracle checks as the default path at the 7B shape for 1, 4 and 16 tokens, on small, odd and fp32 shapes (rows
+    shorter than one chunk of keys, K = F, ranges that end inside a 32-channel word), and on one workspace reused
+    with tied gate values."""
+    import os
+    import subprocess
+    code = ("import tests.test_gpu_parity as t\n"
+            "from paper_2511_09323_amd.configs import CONFIGS\n"
+            "c = CONFIGS['cfg3']\n"
+            "for B in (1, 4, 16):\n"
+            "    t.run_decode_case('cfg3-select-gather', 3, B, c.d, c.F, c.K, 'bf16', x_seed_offset=B)\n"
+            "for B, d, F, K, dt in ((3, 64, 100, 9, 'bf16'), (2, 36, 50, 50, 'f32'), (9, 1024, 333, 40, 'bf16'),\n"
+            "                       (16, 2048, 1000, 125, 'bf16'), (1, 512, 1376, 172, 'f32'), (4, 768, 2048, 256, 'bf16'),\n"
+            "                       (5, 256, 20000, 2500, 'bf16')):\n"
+            "    t.run_decode_case('small-select-gather', 94, B, d, F, K, dt)\n"
+            "for B in (1, 4, 16):\n"
+            "    t.run_decode_reuse_case(B, 1024, 2752, 344)\n"
+            "print('ok')\n")
+    env = dict(os.environ, MOC_DECODE_SELECT_GATHER="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
+
+
 def run_decode_reuse_case(B, d, F, K):
     """Three decode calls on ONE workspace with different inputs, then the first again: every result must
     equal that of a fresh workspace bit for bit (nothing a call leaves in the workspace may leak into the
