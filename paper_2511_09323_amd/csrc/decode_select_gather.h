@@ -14,8 +14,9 @@
 // Measured at the 7B shape (d 4096, d_ffn 11008, K 1376, cold weights): the launch takes 27 us where the selection
 // kernel and the gather take 11 + 15 us, and the call 46 / 62 / 80 us against 43 / 58 / 81 us for 1 / 4 / 16 tokens: the
 // search is a chain of dependent steps that eight wavefronts do no faster than the selection kernel's sixteen, and the
-// saved launch boundary does not pay for it.  The library therefore uses this kernel only on request
-// (MOC_DECODE_SELECT_GATHER=1).
+// saved launch boundary does not pay for it.  (The same search as a selection kernel of its own, 1024 threads per
+// token, takes 14 us against 11 us for the digit passes of the training Top-K kernel.)  The library therefore uses
+// this kernel only on request (MOC_DECODE_SELECT_GATHER=1).
 //
 // Same decision rule as everywhere in the library: fp32 gate values, larger first, ties to the lower channel,
 // -0 = +0.  512 threads; needs d <= 64 * (16 / sizeof(E)) * NIT, F <= NCH * 2048 and ceil(F / P) <= 2048.
