@@ -260,6 +260,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
     };
 
     u32x4_t ga[NSETS][LA], gb[NSETS][LB];   // NSETS slices in flight from global memory
+    [[maybe_unused]] uint32_t gz[NSETS];    // TAILMODE 1: which of a set's chunks are to be zeroed (A chunks in bits 0 .. LA-1, then B)
     // global -> registers for the kt-th k-slice of this workgroup's share of tile t (clamped to the last one so
     // the loop body has no branch)
     auto fetch = [&](const Ctx& t, int buf, int kt) {
@@ -269,6 +270,10 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         const int kwant = (seg ? kt - t.nk0 : kt) * BK;                                  // first k still to accumulate
         const int kfrom = TAILMODE == 1 ? min(kwant, ((klen + 7) & ~7) - BK) : kwant;   // first k read
         const int klast = klen - 1 - kfrom;                                              // last valid k row of this slice
+        // TAILMODE 1: the chunks of this slice that lie before the part still to accumulate or past the end are
+        // zeroed when the slice goes to LDS, not here: a select on a value just loaded would make the wavefront
+        // wait for the load at once and undo the prefetch
+        [[maybe_unused]] uint32_t zero = 0;
         const bf16_t* ap = (seg ? t.ap2 : t.ap) + (AKM ? (int64_t)kfrom * t.lda : (int64_t)kfrom);
         const bf16_t* bp = (seg ? t.bp2 : t.bp) + (BKM ? (int64_t)kfrom * t.ldb : (int64_t)kfrom);
 #pragma unroll
@@ -279,7 +284,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
             ga[buf][i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(ap) + (uint32_t)off * 2u);
             if (TAILMODE == 1) {
                 const int k = kfrom + a_k[i];
-                if (k < kwant || k >= klen) ga[buf][i] = u32x4_t{0, 0, 0, 0};
+                if (k < kwant || k >= klen) zero |= 1u << i;
             }
         }
 #pragma unroll
@@ -289,16 +294,25 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
             gb[buf][i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(bp) + (uint32_t)off * 2u);
             if (TAILMODE == 1) {
                 const int k = kfrom + b_k[i];
-                if (k < kwant || k >= klen) gb[buf][i] = u32x4_t{0, 0, 0, 0};
+                if (k < kwant || k >= klen) zero |= 1u << (LA + i);
             }
         }
+        if (TAILMODE == 1) gz[buf] = zero;
     };
     auto stash = [&](int buf, int stage) {
         unsigned char* base = smem + stage * Cfg::kStage;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4_t*>(base + a_lds[i]) = ga[buf][i];
+        for (int i = 0; i < LA; ++i) {
+            u32x4_t v = ga[buf][i];
+            if (TAILMODE == 1 && ((gz[buf] >> i) & 1u)) v = u32x4_t{0, 0, 0, 0};
+            *reinterpret_cast<u32x4_t*>(base + a_lds[i]) = v;
+        }
 #pragma unroll
-        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4_t*>(base + b_lds[i]) = gb[buf][i];
+        for (int i = 0; i < LB; ++i) {
+            u32x4_t v = gb[buf][i];
+            if (TAILMODE == 1 && ((gz[buf] >> (LA + i)) & 1u)) v = u32x4_t{0, 0, 0, 0};
+            *reinterpret_cast<u32x4_t*>(base + b_lds[i]) = v;
+        }
     };
 
     f32x16_t acc[TM][TN];
