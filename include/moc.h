@@ -52,7 +52,8 @@
  *    measured shapes, kept for study); MOC_GEMM_PERSISTENT=0 launches one workgroup per GEMM tile
  *    instead of one per compute unit looping over tiles; MOC_GEMM_STREAMK=1 lets the training products
  *    whose whole tiles leave part of the chip idle split their work along the contraction (needs a
- *    larger workspace; slower as measured); MOC_BWD_EPILOGUE=1 applies the backward's
+ *    larger workspace; slower as measured; MOC_GEMM_STREAMK_SPIN=n bounds the polls a workgroup spends
+ *    waiting for a neighbour's share before it multiplies that share itself); MOC_BWD_EPILOGUE=1 applies the backward's
  *    pointwise step in the dZ' product's epilogue instead of a kernel of its own (slower as measured);
  *    MOC_GROUPED_SPARSE=1 runs the down projection of moc_ffn_fwd_grouped with a <= 2 on the
  *    structured-sparse matrix instruction (bf16; needs a larger workspace; not faster as measured).

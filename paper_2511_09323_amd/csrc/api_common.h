@@ -82,6 +82,7 @@ struct Options {          // environment, read once when the library is loaded
     int bwd_epilogue;     // MOC_BWD_EPILOGUE=1: backward pointwise step inside the dZ' GEMM's epilogue (mask + prefix tables) instead of the expansion kernel
     int decode_select_gather;  // MOC_DECODE_SELECT_GATHER=1: row-wide decode with the selection repeated inside every gather workgroup instead of a launch of its own (not faster as measured)
     int grouped_sparse;   // MOC_GROUPED_SPARSE=1: down projection of MoC_{a:b}, a <= 2, on the structured-sparse matrix instruction (not faster as measured)
+    int gemm_streamk_spin;  // MOC_GEMM_STREAMK_SPIN=n: polls before a workgroup of a split product stops waiting for its neighbour's share and multiplies it itself (0 in a test of that path)
     int gemm_streamk;     // MOC_GEMM_STREAMK=1: split GEMM work along the contraction where whole tiles leave part of the chip idle (measured slower)
     int gemm_persistent;  // MOC_GEMM_PERSISTENT=0: one workgroup per GEMM tile instead of one per compute unit walking over tiles
     int decode_persistent;  // MOC_DECODE_PERSISTENT=1: row-wide decode as one persistent launch (measured slower than the separate launches)

@@ -40,7 +40,7 @@ hipError_t launch_mfma_tail(const MfmaProblem& pr, const Epi& epi, hipStream_t s
 // at compile time (they must match pr.A.km / pr.B.km).  bf16 problems that satisfy the MFMA
 // kernel's assumptions go to the matrix cores, everything else to the generic kernel.
 inline StreamKArgs streamk_args(const StreamKArea& a, int nk) {
-    return StreamKArgs{a.part, a.flag, next_streamk_tag(), std::max(1, nk / 8), 1 << 20};
+    return StreamKArgs{a.part, a.flag, next_streamk_tag(), std::max(1, nk / 8), std::max(0, options().gemm_streamk_spin)};
 }
 inline int streamk_workgroups() { return std::min(persistent_workgroups(), kStreamKSlots) / 8 * 8; }
 

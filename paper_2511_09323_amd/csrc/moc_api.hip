@@ -66,7 +66,7 @@ static int env_int(const char* name, int dflt) {
 Options::Options()
     : force_generic(env_int("MOC_FORCE_GENERIC", 0)), tile(env_int("MOC_GEMM_TILE", 0)),
       decode_fused(env_int("MOC_DECODE_FUSED", 1)), decode_fused_p(env_int("MOC_DECODE_FUSED_P", 0)),
-      bwd_epilogue(env_int("MOC_BWD_EPILOGUE", 0)), decode_select_gather(env_int("MOC_DECODE_SELECT_GATHER", 0)), grouped_sparse(env_int("MOC_GROUPED_SPARSE", 0)), gemm_streamk(env_int("MOC_GEMM_STREAMK", 0)), gemm_persistent(env_int("MOC_GEMM_PERSISTENT", 1)), decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
+      bwd_epilogue(env_int("MOC_BWD_EPILOGUE", 0)), decode_select_gather(env_int("MOC_DECODE_SELECT_GATHER", 0)), grouped_sparse(env_int("MOC_GROUPED_SPARSE", 0)), gemm_streamk_spin(env_int("MOC_GEMM_STREAMK_SPIN", 1 << 20)), gemm_streamk(env_int("MOC_GEMM_STREAMK", 0)), gemm_persistent(env_int("MOC_GEMM_PERSISTENT", 1)), decode_persistent(env_int("MOC_DECODE_PERSISTENT", 0)) {}
 static const Options g_options;
 const Options& options() { return g_options; }
 

@@ -471,6 +471,14 @@ def test_gemms_split_along_the_contraction():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
+    # the path a workgroup takes when its neighbour's share does not arrive: with no polls at all every workgroup
+    # multiplies the rest of its last tile itself (the host forces this; nothing waits, nothing hangs)
+    code2 = ("import tests.test_gpu_parity as t\n"
+             "t.run_fwd_bwd_case('ragged-split-no-wait', 93, 8100, 544, 2500, 300, 'bf16')\n"
+             "print('ok')\n")
+    env2 = dict(env, MOC_GEMM_STREAMK_SPIN="0")
+    r = subprocess.run([sys.executable, "-c", code2], cwd=root, env=env2, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-3000:] + r.stderr[-3000:]
 
 
 def test_generic_kernels_serve_bf16_when_forced():
