@@ -223,14 +223,15 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         }
     }
 
-    // ---- tile order inside a problem: bands of 8 tile-rows, column by column inside a band, so that a
+    // ---- tile order inside a problem: bands of GROUP tile-rows, column by column inside a band, so that a
     //      contiguous range of tiles (one XCD's share) touches few distinct operand panels.
     auto setup = [&](Ctx& t, int item, int& z) {
         const int mapped = (xcd_map && !SK) ? xcd_contiguous_index(item, item_total) : item;
         z = mapped / nblk;
         const int logical = mapped - z * nblk;
         const MfmaProblem& pr = prs[z];
-        constexpr int GROUP = 8;
+        constexpr int GROUP = 4;      // measured at the 1B shape: band heights 2 / 4 / 6 / 8 / 16 give 1.591 / 1.596 / 1.599 / 1.605 /
+                                      // 1.619 ms per layer step and 425 / 280 / 312 / 291 / 463 MB beyond L2 for the gate product
         const int band = logical / (GROUP * tiles_n);
         const int first_m = band * GROUP;
         const int gsz = min(tiles_m - first_m, GROUP);
