@@ -4,8 +4,11 @@
 A step is one training forward + backward of one MoC FFN layer (all kernels of moc_ffn_fwd and
 moc_ffn_bwd) over one batch of seeded synthetic tokens at the "1B shape" (T 8192, d 2048,
 d_ff 5461, K 683, bf16 with fp32 accumulation), inputs resident in HBM.  The JSON line also
-carries the decode leg at the "7B shape" (effective HBM GB/s, cold weights), a per-kernel
-breakdown, the roofline entry of the gate GEMM and the CPU oracle timed on a bounded sample.
+carries the decode leg at the "7B shape" (effective HBM GB/s, cold weights, with the dense FFN through
+the same entry point beside it), a per-kernel breakdown (durations from HIP events that the library
+records around every launch on the launch stream), the roofline object of the dominant kernel with
+entries for the gate GEMM and the whole decode call, the two small configurations, the prefill
+stack, the grouped and MoE-expert variants, and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
