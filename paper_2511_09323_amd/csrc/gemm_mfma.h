@@ -173,7 +173,7 @@ __device__ __forceinline__ int streamk_start(int r, int ranks, int units, int nk
 // global loads of the next tile's first two k-slices before it writes the current tile out, so that the
 // epilogue and the next prologue overlap; one barrier separates the epilogue's use of the stage memory
 // from the next tile's staging.
-template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS, bool SK = false>
+template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS, bool SK = false, bool MULTI = true>
 __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, const Epi* epis, int tiles_m, int tiles_n,
                                                      int item_first, int item_stride, int item_total, bool xcd_map,
                                                      const StreamKArgs* sk = nullptr) {
@@ -230,8 +230,10 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
         z = mapped / nblk;
         const int logical = mapped - z * nblk;
         const MfmaProblem& pr = prs[z];
-        constexpr int GROUP = 4;      // measured at the 1B shape: band heights 2 / 4 / 6 / 8 / 16 give 1.591 / 1.596 / 1.599 / 1.605 /
-                                      // 1.619 ms per layer step and 425 / 280 / 312 / 291 / 463 MB beyond L2 for the gate product
+        // band height, measured: at the 1B shape (22 tile columns) heights 2 / 4 / 6 / 8 / 16 give 1.591 / 1.596 / 1.599 / 1.605 /
+        // 1.619 ms per layer step and 425 / 280 / 312 / 291 / 463 MB beyond L2 for the gate product; at the 7B shape (43 tile
+        // columns) 8 is ahead of 4 and 2 (gate + up 1.285 / 1.294 / 1.299 ms)
+        const int GROUP = tiles_n >= 32 ? 8 : 4;
         const int band = logical / (GROUP * tiles_n);
         const int first_m = band * GROUP;
         const int gsz = min(tiles_m - first_m, GROUP);
@@ -478,7 +480,7 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
 
         // ---- the next tile's first two slices go out before this tile is written
         int next_item = item + item_stride;
-        bool more = next_item < item_total;
+        bool more = MULTI && next_item < item_total;      // (MULTI = false: a single tile, the walk over tiles compiled out)
         [[maybe_unused]] bool contributed = false;
         if constexpr (SK) {
             u += nk;
@@ -582,8 +584,8 @@ __device__ __forceinline__ void gemm_bf16_mfma_tiles(const MfmaProblem* prs, con
 template <int BM, int BN, bool AKM, bool BKM, int TAILMODE, class Epi, int NWV, int NSETS>
 __device__ __forceinline__ void gemm_bf16_mfma_tile(const MfmaProblem& pr, int tiles_m, int tiles_n, const Epi& epi,
                                                     int logical) {
-    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS>(&pr, &epi, tiles_m, tiles_n, logical, 1 << 30,
-                                                                      tiles_m * tiles_n, false);
+    gemm_bf16_mfma_tiles<BM, BN, AKM, BKM, TAILMODE, Epi, NWV, NSETS, false, false>(&pr, &epi, tiles_m, tiles_n, logical, 1 << 30,
+                                                                                    tiles_m * tiles_n, false);
 }
 
 // The grid is either one workgroup per tile or, when there are more tiles than the chip holds workgroups,
